@@ -1,0 +1,178 @@
+/*
+ * rec.h - C boundary of the DLRM-class forward pass on one MI355X (gfx950).
+ *
+ * One inference query carries, for each of its items ("query size", Sec. II-A),
+ * a vector of dense features and, per embedding table, a variable-length list
+ * of row ids (the pooling factor, Fig. 2(c)); the model (Fig. 2(a), Table I)
+ * returns one click-through score per item.  rec_forward() computes that for a
+ * batch of fused items ("query fusion", Sec. II-B):
+ *
+ *   offsets   = exclusive scan of the pooling lengths
+ *   pooled    = per (sample, table): sum of the gathered rows
+ *               (SparseNet; "Gather-Reduce" / SLS, Sec. VI-B)
+ *   x0        = Bottom-FC(dense)                  (DenseNet, Table I)
+ *   z         = [x0, <v_i, v_j> for i > j] over v = [x0, pooled_0, ...]
+ *               (pairwise-dot interaction of the DLRM model the paper cites)
+ *   logit     = Predict-FC(z)                     (DenseNet, Table I)
+ *
+ * Bottom-FC runs independently of the SparseNet and Predict-FC waits for both
+ * (Sec. III-A).  Element-wise work (bias, ReLU, narrowing, concatenation) is
+ * fused into the producing kernels (Sec. IV-A, operator fusion).
+ *
+ * Conventions
+ *   - Every pointer named dev_* is DEVICE memory owned by the caller and
+ *     borrowed by the library; it must stay valid while the model uses it.
+ *     The library itself allocates no device memory.
+ *   - `stream` arguments are a hipStream_t passed as void* (NULL = the null
+ *     stream).  rec_forward() only enqueues work on that stream.
+ *   - Every call returns a rec_status; nothing aborts or throws.
+ *   - A model is not thread-safe; forwards of one model that overlap on the
+ *     device race on its workspace.
+ */
+#ifndef REC_H
+#define REC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported symbol (the library is built with hidden visibility by default). */
+#define REC_API __attribute__((visibility("default")))
+
+typedef struct rec_model rec_model;
+
+typedef enum {
+    REC_OK = 0,
+    REC_ERR_ARG = 1,         /* null pointer, id out of range, bad enum          */
+    REC_ERR_SHAPE = 2,       /* layer widths do not chain / unsupported emb_dim  */
+    REC_ERR_STATE = 3,       /* call made before what it depends on              */
+    REC_ERR_LENGTHS = 4,     /* device: negative length, or sum(lengths) != nnz  */
+    REC_ERR_INDEX_RANGE = 5, /* device: a row id outside [0, rows)               */
+    REC_ERR_OVERFLOW = 6,    /* a count does not fit the 32-bit index math       */
+    REC_ERR_DEVICE = 7       /* a HIP call failed                                */
+} rec_status;
+
+typedef enum { REC_F32 = 0, REC_F16 = 1 } rec_dtype;
+
+/* Which stack a layer belongs to. */
+enum { REC_BOTTOM = 0, REC_TOP = 1 };
+
+/* Intermediate buffers rec_debug_get() can expose (all inside the workspace). */
+enum {
+    REC_DBG_OFFSETS = 0,   /* int32 [T*B + 1], table-major                       */
+    REC_DBG_POOLED = 1,    /* fp32  [B][T][D]                                    */
+    REC_DBG_BOTTOM_OUT = 2,/* fp32  [B][D]                                       */
+    REC_DBG_INTERACT = 3   /* bf16  [B][ld], ld = *ld_out; columns >= width are 0 */
+};
+
+/* Stages timed by rec_set_profiling(). */
+enum {
+    REC_STAGE_SCAN = 0, REC_STAGE_POOL = 1, REC_STAGE_BOTTOM = 2,
+    REC_STAGE_INTERACT = 3, REC_STAGE_TOP = 4, REC_NUM_STAGES = 5
+};
+
+/*
+ * Model shape (Table I columns: # of Embs, Emb Size, Bottom-FC, Predict-FC).
+ *   rows[t]         rows of table t, each < 2^31
+ *   emb_dim         D; D * sizeof(element) must be 16 * 2^k bytes, k = 0..6
+ *   bottom_widths   n_bottom + 1 entries: num_dense, ..., emb_dim
+ *   top_widths      n_top + 1 entries: emb_dim + T(T+1)/2, ..., 1
+ *   max_batch       largest batch rec_forward() will be given
+ *   max_nnz         largest total number of ids per batch, < 2^31
+ * The arrays are copied; they need not outlive rec_create().
+ */
+typedef struct {
+    int32_t num_tables;
+    int32_t emb_dim;
+    const int64_t *rows;
+    int32_t table_dtype;          /* rec_dtype */
+    int32_t num_dense;
+    int32_t n_bottom;
+    const int32_t *bottom_widths;
+    int32_t n_top;
+    const int32_t *top_widths;
+    int32_t max_batch;
+    int64_t max_nnz;
+} rec_config;
+
+/* Validates the shape and builds the host-side model.  No device work.
+ * REC_ERR_ARG (null / non-positive counts), REC_ERR_SHAPE (width chain,
+ * emb_dim), REC_ERR_OVERFLOW (rows, max_nnz or T*max_batch >= 2^31). */
+REC_API rec_status rec_create(const rec_config *cfg, rec_model **out);
+
+/* Frees the host-side model.  Device buffers stay the caller's. */
+REC_API void rec_destroy(rec_model *m);
+
+/* Bytes of device workspace the model needs (offsets, pooled vectors,
+ * activations, error record); 0 if m is null. */
+REC_API size_t rec_workspace_bytes(const rec_model *m);
+
+/* Hands the model its workspace: dev_ptr is 256-byte aligned device memory of
+ * at least rec_workspace_bytes().  Clears the device error record on `stream`
+ * and waits for it.  REC_ERR_ARG if too small or misaligned. */
+REC_API rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *stream);
+
+/* Registers table `table`: dev_rows is [rows[table]][emb_dim], row-major, of
+ * the configured dtype, 16-byte aligned.  Needs a bound workspace
+ * (REC_ERR_STATE otherwise); copies one descriptor to the device and waits. */
+REC_API rec_status rec_load_tables(rec_model *m, int32_t table, const void *dev_rows);
+
+/* Bytes of the packed form of one layer (bf16 weights padded to the tile grid
+ * followed by fp32 bias); 0 on a bad layer id. */
+REC_API size_t rec_mlp_packed_bytes(const rec_model *m, int32_t which, int32_t layer);
+
+/* Packs layer `layer` of stack `which`: dev_W is fp32 [out][in] row-major,
+ * dev_b fp32 [out]; dev_packed (256-byte aligned, rec_mlp_packed_bytes()) receives
+ * the weights rounded to bf16 (nearest even) and zero padded.  Enqueued on
+ * `stream`; dev_W / dev_b may be released once the stream has passed it,
+ * dev_packed is borrowed for the life of the model. */
+REC_API rec_status rec_load_mlp(rec_model *m, int32_t which, int32_t layer, const float *dev_W,
+                        const float *dev_b, void *dev_packed, void *stream);
+
+/*
+ * Enqueues one forward pass on `stream`.
+ *   dev_dense    fp32  [batch][num_dense]
+ *   dev_indices  int32 [nnz], bags concatenated table-major
+ *   dev_lengths  int32 [num_tables * batch], entry t*batch + b = bag (t, b)
+ *   dev_logits   fp32  [batch]  (pre-sigmoid)
+ * No allocation, no synchronisation, no host read of device data.
+ * Host-checkable faults return at once: REC_ERR_ARG (null, batch < 0 or
+ * > max_batch, nnz < 0 or > max_nnz), REC_ERR_STATE (workspace, a table or a
+ * layer missing).  batch == 0 enqueues nothing.  Faults only the device can
+ * see never stop the pass: a negative length counts as 0, an id outside its
+ * table contributes zero, ids past `nnz` are not read; each sets a sticky
+ * device error record that rec_check() reports.
+ * An empty bag pools to zero; duplicate ids count with multiplicity.
+ */
+REC_API rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_indices,
+                       const int32_t *dev_lengths, int32_t batch, int64_t nnz,
+                       float *dev_logits, void *stream);
+
+/* Waits for `stream`, reads and clears the device error record.  Returns REC_OK,
+ * REC_ERR_LENGTHS (first_bad_pos = position in lengths of the first negative
+ * one, or -1 when only the total disagreed with nnz) or REC_ERR_INDEX_RANGE
+ * (first_bad_pos = smallest position in indices of an id outside its table).
+ * Length faults win over index faults.  first_bad_pos may be null. */
+REC_API rec_status rec_check(rec_model *m, void *stream, int64_t *first_bad_pos);
+
+/* Device pointer of an intermediate buffer of the last forward (REC_DBG_*).
+ * ld_out (may be null) receives the row stride in elements where it applies. */
+REC_API rec_status rec_debug_get(rec_model *m, int32_t what, const void **dev_ptr, int64_t *ld_out);
+
+/* Per-stage timing.  rec_set_profiling(m, slots) with slots > 0 makes
+ * rec_forward() bracket each stage with HIP events on its stream; forward
+ * number i (counted from this call) records into slot i % slots.  slots = 0
+ * switches it off.  rec_stage_ms() waits for the events of `slot` and fills
+ * ms[REC_NUM_STAGES]; REC_ERR_STATE if that slot has not been recorded. */
+REC_API rec_status rec_set_profiling(rec_model *m, int32_t slots);
+REC_API rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms);
+
+REC_API const char *rec_status_string(rec_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REC_H */

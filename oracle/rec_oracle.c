@@ -328,14 +328,22 @@ int oracle_forward(const float *dense, const void *const *tables, int dtype,
 
     /* interaction; h0 = bottom output [B][D] -> h1 = [B][width] */
     oracle_interact(h0, P, B, T, D, h1);
+    /* The interaction output is what the Predict-FC matrix unit is fed with:
+     * the mirror narrows it here, whatever layer consumes it. */
+    if (mode == ORACLE_BF16_MIRROR)
+        for (int64_t i = 0; i < (int64_t)B * width; ++i)
+            h1[i] = oracle_round_bf16(h1[i]);
     if (interact)
         memcpy(interact, h1, (size_t)B * width * sizeof(double));
     { double *tmp = h0; h0 = h1; h1 = tmp; }
 
-    /* Predict-FC: ReLU on all layers but the last */
+    /* Predict-FC: ReLU on all layers but the last.  The last layer has one
+     * output, a dot product per sample rather than a matrix product, so the
+     * bf16 mirror leaves its weights and inputs un-narrowed. */
     for (int l = 0; l < n_top; ++l) {
+        int last = l + 1 == n_top;
         oracle_fc(h0, top_W[l], top_b[l], B, top_widths[l], top_widths[l + 1],
-                  l + 1 < n_top, mode, h1);
+                  !last, last ? ORACLE_EXACT : mode, h1);
         double *tmp = h0; h0 = h1; h1 = tmp;
     }
     if (logits)

@@ -1,0 +1,277 @@
+"""ctypes binding of the C boundary declared in include/rec.h.
+
+Argument marshalling only: every step of the forward pass runs in the HIP
+library.  PyTorch supplies device memory and the stream.  Importing this
+module raises if the library has not been built; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch  # loads the HIP runtime the library binds to
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librec_mi355x.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -m paper_2203_07424_amd.build "
+        "or __graft_entry__.build()); there is no CPU fallback")
+
+_lib = C.CDLL(LIB_PATH)
+
+REC_OK = 0
+REC_ERR_ARG, REC_ERR_SHAPE, REC_ERR_STATE, REC_ERR_LENGTHS = 1, 2, 3, 4
+REC_ERR_INDEX_RANGE, REC_ERR_OVERFLOW, REC_ERR_DEVICE = 5, 6, 7
+REC_F32, REC_F16 = 0, 1
+REC_BOTTOM, REC_TOP = 0, 1
+REC_DBG_OFFSETS, REC_DBG_POOLED, REC_DBG_BOTTOM_OUT, REC_DBG_INTERACT = 0, 1, 2, 3
+REC_NUM_STAGES = 5
+STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top")
+
+EXPORTS = ("rec_create", "rec_destroy", "rec_workspace_bytes", "rec_bind_workspace",
+           "rec_load_tables", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_check",
+           "rec_debug_get", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
+           "rec_synth_fill_table")
+
+
+class rec_config(C.Structure):
+    _fields_ = [("num_tables", C.c_int32), ("emb_dim", C.c_int32),
+                ("rows", C.POINTER(C.c_int64)), ("table_dtype", C.c_int32),
+                ("num_dense", C.c_int32), ("n_bottom", C.c_int32),
+                ("bottom_widths", C.POINTER(C.c_int32)), ("n_top", C.c_int32),
+                ("top_widths", C.POINTER(C.c_int32)), ("max_batch", C.c_int32),
+                ("max_nnz", C.c_int64)]
+
+
+_vp = C.c_void_p
+_lib.rec_create.restype = C.c_int
+_lib.rec_create.argtypes = [C.POINTER(rec_config), C.POINTER(_vp)]
+_lib.rec_destroy.restype = None
+_lib.rec_destroy.argtypes = [_vp]
+_lib.rec_workspace_bytes.restype = C.c_size_t
+_lib.rec_workspace_bytes.argtypes = [_vp]
+_lib.rec_bind_workspace.restype = C.c_int
+_lib.rec_bind_workspace.argtypes = [_vp, _vp, C.c_size_t, _vp]
+_lib.rec_load_tables.restype = C.c_int
+_lib.rec_load_tables.argtypes = [_vp, C.c_int32, _vp]
+_lib.rec_mlp_packed_bytes.restype = C.c_size_t
+_lib.rec_mlp_packed_bytes.argtypes = [_vp, C.c_int32, C.c_int32]
+_lib.rec_load_mlp.restype = C.c_int
+_lib.rec_load_mlp.argtypes = [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp]
+_lib.rec_forward.restype = C.c_int
+_lib.rec_forward.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int64, _vp, _vp]
+_lib.rec_check.restype = C.c_int
+_lib.rec_check.argtypes = [_vp, _vp, C.POINTER(C.c_int64)]
+_lib.rec_debug_get.restype = C.c_int
+_lib.rec_debug_get.argtypes = [_vp, C.c_int32, C.POINTER(_vp), C.POINTER(C.c_int64)]
+_lib.rec_set_profiling.restype = C.c_int
+_lib.rec_set_profiling.argtypes = [_vp, C.c_int32]
+_lib.rec_stage_ms.restype = C.c_int
+_lib.rec_stage_ms.argtypes = [_vp, C.c_int32, C.POINTER(C.c_float)]
+_lib.rec_status_string.restype = C.c_char_p
+_lib.rec_status_string.argtypes = [C.c_int]
+_lib.rec_synth_fill_table.restype = C.c_int
+_lib.rec_synth_fill_table.argtypes = [_vp, C.c_int32, C.c_uint64, C.c_int32, C.c_int64, C.c_int32, _vp]
+
+
+class RecError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def status_string(status: int) -> str:
+    return _lib.rec_status_string(int(status)).decode()
+
+
+def _stream() -> Optional[int]:
+    # Without a device only the host-side argument checks of the library can
+    # run, and those never touch the stream.
+    if not torch.cuda.is_available():
+        return None
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+# Raw entry points, same names as the C boundary; each returns the status.
+def rec_create(num_tables: int, emb_dim: int, rows: Sequence[int], table_dtype: int,
+               num_dense: int, bottom_widths: Sequence[int], top_widths: Sequence[int],
+               max_batch: int, max_nnz: int) -> Tuple[int, Optional[int]]:
+    rows_a = (C.c_int64 * len(rows))(*rows)
+    bw = (C.c_int32 * len(bottom_widths))(*bottom_widths)
+    tw = (C.c_int32 * len(top_widths))(*top_widths)
+    cfg = rec_config(num_tables, emb_dim, rows_a, table_dtype, num_dense, len(bottom_widths) - 1,
+                     bw, len(top_widths) - 1, tw, max_batch, max_nnz)
+    out = _vp()
+    st = _lib.rec_create(C.byref(cfg), C.byref(out))
+    return st, out.value
+
+
+def rec_destroy(m: int) -> None:
+    _lib.rec_destroy(m)
+
+
+def rec_workspace_bytes(m: int) -> int:
+    return int(_lib.rec_workspace_bytes(m))
+
+
+def rec_bind_workspace(m: int, ws: torch.Tensor) -> int:
+    return _lib.rec_bind_workspace(m, ws.data_ptr(), ws.numel() * ws.element_size(), _stream())
+
+
+def rec_load_tables(m: int, table: int, dev_rows: torch.Tensor) -> int:
+    return _lib.rec_load_tables(m, table, dev_rows.data_ptr())
+
+
+def rec_mlp_packed_bytes(m: int, which: int, layer: int) -> int:
+    return int(_lib.rec_mlp_packed_bytes(m, which, layer))
+
+
+def rec_load_mlp(m: int, which: int, layer: int, dev_W: torch.Tensor, dev_b: torch.Tensor,
+                 dev_packed: torch.Tensor) -> int:
+    return _lib.rec_load_mlp(m, which, layer, dev_W.data_ptr(), dev_b.data_ptr(),
+                             dev_packed.data_ptr(), _stream())
+
+
+def rec_forward(m: int, dev_dense, dev_indices, dev_lengths, batch: int, nnz: int, dev_logits) -> int:
+    return _lib.rec_forward(m, _ptr(dev_dense), _ptr(dev_indices), _ptr(dev_lengths), batch, nnz,
+                            _ptr(dev_logits), _stream())
+
+
+def rec_check(m: int) -> Tuple[int, int]:
+    pos = C.c_int64(-1)
+    st = _lib.rec_check(m, _stream(), C.byref(pos))
+    return st, int(pos.value)
+
+
+def rec_debug_get(m: int, what: int) -> Tuple[int, Optional[int], int]:
+    p, ld = _vp(), C.c_int64(0)
+    st = _lib.rec_debug_get(m, what, C.byref(p), C.byref(ld))
+    return st, p.value, int(ld.value)
+
+
+def rec_set_profiling(m: int, slots: int) -> int:
+    return _lib.rec_set_profiling(m, int(slots))
+
+
+def rec_stage_ms(m: int, slot: int = 0) -> Tuple[int, List[float]]:
+    ms = (C.c_float * REC_NUM_STAGES)()
+    st = _lib.rec_stage_ms(m, slot, ms)
+    return st, [float(v) for v in ms]
+
+
+def rec_synth_fill_table(dev_rows: torch.Tensor, seed: int, table: int) -> int:
+    dtype = REC_F16 if dev_rows.dtype == torch.float16 else REC_F32
+    return _lib.rec_synth_fill_table(dev_rows.data_ptr(), dtype, seed, table, dev_rows.shape[0],
+                                     dev_rows.shape[1], _stream())
+
+
+class RecModel:
+    """Owns the device buffers of one model and forwards batches through the library."""
+
+    def __init__(self, num_tables: int, emb_dim: int, rows: Sequence[int], table_dtype: str,
+                 num_dense: int, bottom_widths: Sequence[int], top_widths: Sequence[int],
+                 max_batch: int, max_nnz: int, device: str = "cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the forward pass has no CPU path")
+        self.device = torch.device(device)
+        self.T, self.D, self.F = num_tables, emb_dim, num_dense
+        self.table_dtype = {"f32": torch.float32, "f16": torch.float16}[table_dtype]
+        self.width = top_widths[0]
+        self.n_bottom, self.n_top = len(bottom_widths) - 1, len(top_widths) - 1
+        code = REC_F16 if table_dtype == "f16" else REC_F32
+        st, self.handle = rec_create(num_tables, emb_dim, list(rows), code, num_dense,
+                                     list(bottom_widths), list(top_widths), max_batch, max_nnz)
+        if st != REC_OK:
+            raise RecError(st, "rec_create")
+        self.ws = torch.empty(rec_workspace_bytes(self.handle), dtype=torch.uint8, device=self.device)
+        self._ok(rec_bind_workspace(self.handle, self.ws), "rec_bind_workspace")
+        self.tables: List[Optional[torch.Tensor]] = [None] * num_tables
+        self.packed: dict = {}
+        self.last_batch = 0
+
+    def _ok(self, st: int, where: str) -> None:
+        if st != REC_OK:
+            raise RecError(st, where)
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            torch.cuda.synchronize(self.device)
+            rec_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def load_table(self, t: int, dev_rows: torch.Tensor) -> None:
+        assert dev_rows.is_cuda and dev_rows.is_contiguous() and dev_rows.dtype == self.table_dtype
+        self._ok(rec_load_tables(self.handle, t, dev_rows), "rec_load_tables")
+        self.tables[t] = dev_rows
+
+    def load_mlp(self, which: int, layer: int, W: torch.Tensor, b: torch.Tensor) -> None:
+        W = W.to(self.device, torch.float32).contiguous()
+        b = b.to(self.device, torch.float32).contiguous()
+        packed = torch.empty(rec_mlp_packed_bytes(self.handle, which, layer), dtype=torch.uint8,
+                             device=self.device)
+        self._ok(rec_load_mlp(self.handle, which, layer, W, b, packed), "rec_load_mlp")
+        torch.cuda.current_stream().synchronize()   # W and b may be freed after this
+        self.packed[(which, layer)] = packed
+
+    def forward(self, dense: torch.Tensor, indices: torch.Tensor, lengths: torch.Tensor,
+                logits: Optional[torch.Tensor] = None) -> torch.Tensor:
+        batch = dense.shape[0]
+        if logits is None:
+            logits = torch.empty(batch, dtype=torch.float32, device=self.device)
+        self._ok(rec_forward(self.handle, dense, indices, lengths, batch, indices.numel(), logits),
+                 "rec_forward")
+        self.last_batch = batch
+        return logits
+
+    def check(self) -> Tuple[int, int]:
+        return rec_check(self.handle)
+
+    def set_profiling(self, slots: int) -> None:
+        self._ok(rec_set_profiling(self.handle, slots), "rec_set_profiling")
+
+    def stage_ms(self, slot: int = 0) -> dict:
+        st, ms = rec_stage_ms(self.handle, slot)
+        self._ok(st, "rec_stage_ms")
+        return dict(zip(STAGE_NAMES, ms))
+
+    def _view(self, what: int, nbytes: int) -> Tuple[torch.Tensor, int]:
+        st, p, ld = rec_debug_get(self.handle, what)
+        self._ok(st, "rec_debug_get")
+        off = p - self.ws.data_ptr()
+        return self.ws[off:off + nbytes], ld
+
+    def debug_offsets(self) -> torch.Tensor:
+        n = self.T * self.last_batch + 1
+        raw, _ = self._view(REC_DBG_OFFSETS, 4 * n)
+        return raw.view(torch.int32).clone()
+
+    def debug_pooled(self) -> torch.Tensor:
+        B = self.last_batch
+        raw, _ = self._view(REC_DBG_POOLED, 4 * B * self.T * self.D)
+        return raw.view(torch.float32).view(B, self.T, self.D).clone()
+
+    def debug_bottom_out(self) -> torch.Tensor:
+        B = self.last_batch
+        st, p, ld = rec_debug_get(self.handle, REC_DBG_BOTTOM_OUT)
+        raw, ld = self._view(REC_DBG_BOTTOM_OUT, 4 * B * ld)
+        return raw.view(torch.float32).view(B, ld)[:, :self.D].clone()
+
+    def debug_interact(self) -> torch.Tensor:
+        """bf16 [B, ld]; columns beyond the interaction width are zero padding."""
+        B = self.last_batch
+        st, p, ld = rec_debug_get(self.handle, REC_DBG_INTERACT)
+        raw, ld = self._view(REC_DBG_INTERACT, 2 * B * ld)
+        return raw.view(torch.bfloat16).view(B, ld).clone()

@@ -1,0 +1,296 @@
+// S2 / S4: fully connected layers (Bottom-FC, Predict-FC; Table I) on the
+// bf16 matrix cores, with the element-wise tail fused in (Sec. IV-A): bias,
+// ReLU and the narrowing to bf16 happen in the epilogue, and the first layer
+// narrows its fp32 input while staging it.
+//
+//   C[m][n] = act( sum_k A[m][k] * W[n][k] + bias[n] )
+//
+// Both operands are K-contiguous, which is what v_mfma_f32_32x32x16_bf16 wants:
+// lane l feeds 8 consecutive k of row (l % 32), k-offset 8 * (l / 32).  The
+// weight tile is the first MFMA operand and the activation tile the second, so
+// that each lane ends up with 4 consecutive output features of one sample and
+// can store them as one 8-byte (bf16) or 16-byte (fp32) word.
+//
+// A block of 4 waves computes a BM x BN tile; tiles of A and W go through one
+// LDS buffer each, the next tile's global loads being in flight while the
+// current one is multiplied.
+#include "rec_internal.h"
+
+namespace rec {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int BK = 64;            // k extent of one staged tile
+constexpr int LDS_LD = BK + 8;    // row stride in LDS (elements); 144 B keeps 16-byte reads conflict-free
+constexpr int FC_THREADS = 256;
+
+// 8 consecutive k of one activation row, as bf16.
+template <bool A_F32>
+__device__ inline bf16x8 load_a_chunk(const void *A, long long row, int lda, int k, int K, bool vec_ok)
+{
+    bf16x8 out;
+    if (A_F32) {
+        const float *p = static_cast<const float *>(A) + row * lda + k;
+        if (vec_ok && k + 8 <= K) {
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(p);
+            const f32x4 hi = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                out[i] = (__bf16)lo[i];
+                out[i + 4] = (__bf16)hi[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) out[i] = (__bf16)((k + i < K) ? p[i] : 0.0f);
+        }
+    } else {
+        // bf16 activations live in buffers whose columns up to lda are valid (zero padded).
+        out = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(A) + row * lda + k);
+    }
+    return out;
+}
+
+template <int BM, int BN, bool A_F32, bool OUT_F32>
+__global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__ A, int lda, int M,
+                                                        int K, int Kpad,
+                                                        const __bf16 *__restrict__ W,
+                                                        const float *__restrict__ bias, int relu,
+                                                        void *__restrict__ C, int ldc, int vec_ok)
+{
+    constexpr int WM = BM / 2, WN = BN / 2;     // per-wave tile (2 x 2 waves)
+    constexpr int TM = WM / 32, TN = WN / 32;   // 32 x 32 MFMA tiles per wave
+    constexpr int A_LOADS = BM / 32, W_LOADS = BN / 32;
+
+    __shared__ __attribute__((aligned(16))) __bf16 sA[BM * LDS_LD];
+    __shared__ __attribute__((aligned(16))) __bf16 sW[BN * LDS_LD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    // Staging role: 8 threads cover the 64 k of one row, 32 rows per pass.
+    const int ld_row = tid >> 3, ld_chunk = tid & 7;
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 ra[A_LOADS], rw[W_LOADS];
+    auto fetch = [&](int kt) {
+        const int k = kt * BK + ld_chunk * 8;
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) {
+            int row = m0 + ld_row + 32 * i;
+            row = row < M ? row : M - 1;  // rows past M are computed and dropped
+            ra[i] = load_a_chunk<A_F32>(A, row, lda, k, K, vec_ok);
+        }
+#pragma unroll
+        for (int i = 0; i < W_LOADS; ++i) {
+            const long long row = n0 + ld_row + 32 * i;
+            rw[i] = *reinterpret_cast<const bf16x8 *>(W + row * Kpad + k);
+        }
+    };
+
+    const int nk = Kpad / BK;
+    fetch(0);
+    for (int kt = 0; kt < nk; ++kt) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i)
+            *reinterpret_cast<bf16x8 *>(&sA[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < W_LOADS; ++i)
+            *reinterpret_cast<bf16x8 *>(&sW[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = rw[i];
+        __syncthreads();
+        if (kt + 1 < nk) fetch(kt + 1);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int kofs = kk * 16 + (lane >> 5) * 8;
+            bf16x8 fw[TN], fa[TM];
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+                fw[i] = *reinterpret_cast<const bf16x8 *>(
+                    &sW[(wn * WN + i * 32 + (lane & 31)) * LDS_LD + kofs]);
+#pragma unroll
+            for (int j = 0; j < TM; ++j)
+                fa[j] = *reinterpret_cast<const bf16x8 *>(
+                    &sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]);
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // acc[i][j][r]: feature n = 8 * (r / 4) + 4 * (lane / 32) + r % 4, sample m = lane % 32.
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int m = m0 + wm * WM + j * 32 + (lane & 31);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * WN + i * 32 + 8 * q + 4 * (lane >> 5);
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias + n);
+                f32x4 v;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float x = acc[i][j][4 * q + r] + bv[r];
+                    v[r] = (relu && x < 0.0f) ? 0.0f : x;
+                }
+                if (m < M) {
+                    if (OUT_F32) {
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(C) + (long long)m * ldc + n) = v;
+                    } else {
+                        bf16x4 o;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o[r] = (__bf16)v[r];
+                        *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(C) + (long long)m * ldc + n) = o;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN>
+hipError_t launch_tile(const void *A, bool a_f32, int lda, int M, int K, int Kpad, const void *W,
+                       const float *bias, int Npad, bool relu, void *C, bool out_f32, int ldc,
+                       hipStream_t s)
+{
+    const dim3 grid(Npad / BN, (M + BM - 1) / BM), block(FC_THREADS);
+    const __bf16 *Wb = static_cast<const __bf16 *>(W);
+    // 16-byte loads of fp32 rows need lda % 4 == 0 and an aligned base.
+    const int vec_ok = a_f32 && (lda % 4 == 0) && (reinterpret_cast<uintptr_t>(A) % 16 == 0);
+    const int r = relu ? 1 : 0;
+    if (a_f32 && out_f32)
+        hipLaunchKernelGGL((fc_kernel<BM, BN, true, true>), grid, block, 0, s, A, lda, M, K, Kpad, Wb, bias, r, C, ldc, vec_ok);
+    else if (a_f32)
+        hipLaunchKernelGGL((fc_kernel<BM, BN, true, false>), grid, block, 0, s, A, lda, M, K, Kpad, Wb, bias, r, C, ldc, vec_ok);
+    else if (out_f32)
+        hipLaunchKernelGGL((fc_kernel<BM, BN, false, true>), grid, block, 0, s, A, lda, M, K, Kpad, Wb, bias, r, C, ldc, vec_ok);
+    else
+        hipLaunchKernelGGL((fc_kernel<BM, BN, false, false>), grid, block, 0, s, A, lda, M, K, Kpad, Wb, bias, r, C, ldc, vec_ok);
+    return hipGetLastError();
+}
+
+// Last Predict-FC layer (one output per sample): a plain fp32 dot product with
+// fp32 weights; 8 lanes share a row.  The input is the previous layer's fp32
+// output, or the bf16 interaction output when the stack has a single layer.
+template <bool A_F32>
+__global__ __launch_bounds__(256) void rowdot_kernel(const void *__restrict__ A, int lda, int M,
+                                                     int Kpad, const float *__restrict__ w,
+                                                     const float *__restrict__ bias,
+                                                     float *__restrict__ logits)
+{
+    const int sub = threadIdx.x & 7;
+    const long long m = (long long)blockIdx.x * 32 + (threadIdx.x >> 3);
+    const long long row = m < M ? m : M - 1;
+    float acc = 0.0f;
+    for (int k = sub * 8; k < Kpad; k += 64) {
+        float a[8];
+        if (A_F32) {
+            const float *p = static_cast<const float *>(A) + row * lda + k;
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(p);
+            const f32x4 hi = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = lo[i]; a[i + 4] = hi[i]; }
+        } else {
+            const bf16x8 v = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(A) + row * lda + k);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) a[i] = (float)v[i];
+        }
+        const f32x4 w0 = *reinterpret_cast<const f32x4 *>(w + k);
+        const f32x4 w1 = *reinterpret_cast<const f32x4 *>(w + k + 4);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc += a[i] * w0[i];
+            acc += a[i + 4] * w1[i];
+        }
+    }
+    acc += __shfl_xor(acc, 1, 64);
+    acc += __shfl_xor(acc, 2, 64);
+    acc += __shfl_xor(acc, 4, 64);
+    if (sub == 0 && m < M) logits[m] = acc + bias[0];
+}
+
+// One-output layer: fp32 weights [Kpad], zero padded, and its bias.
+__global__ __launch_bounds__(256) void pack_dot_kernel(const float *__restrict__ W,
+                                                       const float *__restrict__ b, int K, int Kpad,
+                                                       float *__restrict__ Wp, float *__restrict__ bp)
+{
+    for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < Kpad; k += gridDim.x * blockDim.x)
+        Wp[k] = k < K ? W[k] : 0.0f;
+    if (blockIdx.x == 0 && threadIdx.x == 0) bp[0] = b[0];
+}
+
+__global__ __launch_bounds__(256) void pack_fc_kernel(const float *__restrict__ W,
+                                                      const float *__restrict__ b, int N, int K,
+                                                      int Npad, int Kpad, __bf16 *__restrict__ Wp,
+                                                      float *__restrict__ bp)
+{
+    const long long total = (long long)Npad * Kpad;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const int n = (int)(i / Kpad), k = (int)(i % Kpad);
+        Wp[i] = (__bf16)((n < N && k < K) ? W[(long long)n * K + k] : 0.0f);
+        if (k == 0) bp[n] = n < N ? b[n] : 0.0f;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_fc(const void *A, bool a_f32, int lda, int M, int K, int Kpad, const void *W,
+                     const float *bias, int Npad, bool relu, void *C, bool out_f32, int ldc,
+                     hipStream_t s)
+{
+    if (M <= 0) return hipSuccess;
+    if (Kpad % BK != 0 || Npad % 64 != 0) return hipErrorInvalidValue;
+    // Large tiles only where they still give every compute unit a block.
+    const long long big_blocks = (long long)(Npad / 128) * ((M + 127) / 128);
+    if (Npad % 128 == 0 && big_blocks >= 256)
+        return launch_tile<128, 128>(A, a_f32, lda, M, K, Kpad, W, bias, Npad, relu, C, out_f32, ldc, s);
+    return launch_tile<64, 64>(A, a_f32, lda, M, K, Kpad, W, bias, Npad, relu, C, out_f32, ldc, s);
+}
+
+hipError_t launch_rowdot(const void *A, bool a_f32, int lda, int M, int Kpad, const float *w,
+                         const float *bias, float *logits, hipStream_t s)
+{
+    if (M <= 0) return hipSuccess;
+    const dim3 grid((M + 31) / 32), block(256);
+    if (a_f32)
+        hipLaunchKernelGGL(rowdot_kernel<true>, grid, block, 0, s, A, lda, M, Kpad, w, bias, logits);
+    else
+        hipLaunchKernelGGL(rowdot_kernel<false>, grid, block, 0, s, A, lda, M, Kpad, w, bias, logits);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_dot(const float *W, const float *b, int K, int Kpad, float *W_packed,
+                           float *bias_packed, hipStream_t s)
+{
+    hipLaunchKernelGGL(pack_dot_kernel, dim3((Kpad + 255) / 256), dim3(256), 0, s, W, b, K, Kpad,
+                       W_packed, bias_packed);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack_fc(const float *W, const float *b, int N, int K, int Npad, int Kpad,
+                          void *W_packed, float *bias_packed, hipStream_t s)
+{
+    const long long total = (long long)Npad * Kpad;
+    const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(pack_fc_kernel, dim3(blocks), dim3(256), 0, s, W, b, N, K, Npad, Kpad,
+                       static_cast<__bf16 *>(W_packed), bias_packed);
+    return hipGetLastError();
+}
+
+}  // namespace rec

@@ -1,0 +1,159 @@
+// S1: embedding-bag pooling (SparseLengthsSum; "Gather-Reduce", Sec. VI-B).
+//
+// pooled[b][t][:] = sum of rows E_t[id][:] over the ids of bag (t, b).
+//
+// One 64-lane wavefront per bag.  A row is D * sizeof(element) bytes; a lane
+// moves 16 bytes (one 128-bit load), so LPR = rowbytes / 16 lanes cover a row
+// and one wave-wide load fetches RPW = 64 / LPR different rows of the bag.
+// The wave reads 64 ids with one coalesced load, hands them out by lane
+// shuffle, keeps several row loads in flight, accumulates in fp32 and folds the
+// RPW partial sums in a fixed order, so results do not vary from run to run.
+// The work is pure random-gather traffic: HBM bandwidth bounds it.
+#include <hip/hip_fp16.h>
+
+#include "rec_internal.h"
+
+namespace rec {
+
+namespace {
+
+constexpr int POOL_WAVES = 4;   // bags per block
+constexpr int POOL_UNROLL = 4;  // row loads in flight per lane and step
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+template <bool HALF>
+struct Acc {
+    static constexpr int N = HALF ? 8 : 4;
+    float v[N];
+};
+
+template <bool HALF>
+__device__ inline void accumulate(Acc<HALF> &a, const f32x4 raw, bool ok)
+{
+    if (HALF) {
+        const f16x8 h = __builtin_bit_cast(f16x8, raw);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a.v[i] += ok ? (float)h[i] : 0.0f;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a.v[i] += ok ? raw[i] : 0.0f;
+    }
+}
+
+template <int LPR, bool HALF>
+__global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
+    const TableDesc *__restrict__ tables, const int32_t *__restrict__ indices,
+    const int32_t *__restrict__ offsets, float *__restrict__ pooled, int B, int T, int nbags,
+    ErrRecord *err)
+{
+    constexpr int RPW = 64 / LPR;
+    constexpr int ROWBYTES = LPR * 16;
+    constexpr int NACC = HALF ? 8 : 4;
+    constexpr int D = ROWBYTES / (HALF ? 2 : 4);
+
+    const int lane = threadIdx.x & 63;
+    int bag = blockIdx.x * POOL_WAVES + (threadIdx.x >> 6);
+    if (bag >= nbags) return;
+    bag = __builtin_amdgcn_readfirstlane(bag);
+    const int t = bag / B;
+    const int b = bag - t * B;
+    const int start = offsets[bag];
+    const int end = offsets[bag + 1];
+    const char *base = static_cast<const char *>(tables[t].base);
+    const long long rows = tables[t].rows;
+
+    const int sub = lane / LPR;  // which of the RPW rows of a wave-wide load
+    const int chunk = lane % LPR;
+    const char *lane_base = base + chunk * 16;
+
+    Acc<HALF> acc;
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc.v[i] = 0.0f;
+
+    int ids = -1;
+    if (start + lane < end) ids = indices[start + lane];
+    for (int k0 = start; k0 < end; k0 += 64) {
+        const int n = min(64, end - k0);
+        int cur = ids;
+        // Ids outside the table contribute zero and leave a record.
+        if (lane < n && (unsigned long long)(long long)cur >= (unsigned long long)rows) {
+            atomicMin(&err->first_bad_idx, (unsigned long long)(k0 + lane));
+            atomicOr(&err->flags, ERR_INDEX_RANGE);
+            cur = -1;
+        }
+        // Next 64 ids, requested before the row loads of this step.
+        ids = -1;
+        if (k0 + 64 + lane < end) ids = indices[k0 + 64 + lane];
+
+        const int steps = (n + RPW - 1) / RPW;  // wave-wide loads this chunk needs
+        for (int j = 0; j < steps; j += POOL_UNROLL) {
+            f32x4 raw[POOL_UNROLL];
+            bool ok[POOL_UNROLL];
+#pragma unroll
+            for (int u = 0; u < POOL_UNROLL; ++u) {
+                const int slot = (j + u) * RPW + sub;  // < 64 whenever j + u < LPR
+                const int id = __shfl(cur, slot & 63, 64);
+                ok[u] = (j + u) < steps && id >= 0;
+                const long long row = ok[u] ? id : 0;
+                raw[u] = *reinterpret_cast<const f32x4 *>(lane_base + row * ROWBYTES);
+            }
+#pragma unroll
+            for (int u = 0; u < POOL_UNROLL; ++u) accumulate<HALF>(acc, raw[u], ok[u]);
+        }
+    }
+
+    // Fold the RPW partial sums: lanes l and l ^ m hold the same columns.
+#pragma unroll
+    for (int m = LPR; m < 64; m <<= 1) {
+#pragma unroll
+        for (int i = 0; i < NACC; ++i) acc.v[i] += __shfl_xor(acc.v[i], m, 64);
+    }
+    if (sub == 0) {
+        float *out = pooled + ((long long)b * T + t) * D + chunk * NACC;
+#pragma unroll
+        for (int i = 0; i < NACC; i += 4) {
+            f32x4 o = {acc.v[i], acc.v[i + 1], acc.v[i + 2], acc.v[i + 3]};
+            *reinterpret_cast<f32x4 *>(out + i) = o;
+        }
+    }
+}
+
+template <int LPR>
+hipError_t launch_lpr(bool half, const TableDesc *tables, int T, int B, const int32_t *indices,
+                      const int32_t *offsets, float *pooled, ErrRecord *err, hipStream_t s)
+{
+    const int nbags = T * B;
+    const dim3 grid((nbags + POOL_WAVES - 1) / POOL_WAVES), block(POOL_WAVES * 64);
+    if (half)
+        hipLaunchKernelGGL((pool_kernel<LPR, true>), grid, block, 0, s, tables, indices, offsets,
+                           pooled, B, T, nbags, err);
+    else
+        hipLaunchKernelGGL((pool_kernel<LPR, false>), grid, block, 0, s, tables, indices, offsets,
+                           pooled, B, T, nbags, err);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_pool(const TableDesc *tables, int dtype, int T, int D, int B,
+                       const int32_t *indices, const int32_t *offsets, float *pooled,
+                       ErrRecord *err, hipStream_t s)
+{
+    if (T <= 0 || B <= 0) return hipSuccess;
+    const bool half = dtype == REC_F16;
+    const int rowbytes = D * (half ? 2 : 4);
+    switch (rowbytes / 16) {
+    case 1: return launch_lpr<1>(half, tables, T, B, indices, offsets, pooled, err, s);
+    case 2: return launch_lpr<2>(half, tables, T, B, indices, offsets, pooled, err, s);
+    case 4: return launch_lpr<4>(half, tables, T, B, indices, offsets, pooled, err, s);
+    case 8: return launch_lpr<8>(half, tables, T, B, indices, offsets, pooled, err, s);
+    case 16: return launch_lpr<16>(half, tables, T, B, indices, offsets, pooled, err, s);
+    case 32: return launch_lpr<32>(half, tables, T, B, indices, offsets, pooled, err, s);
+    case 64: return launch_lpr<64>(half, tables, T, B, indices, offsets, pooled, err, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace rec

@@ -1,0 +1,377 @@
+// C boundary of the forward pass: model bookkeeping on the host and the fixed
+// launch sequence  scan -> pool -> Bottom-FC -> interaction -> Predict-FC.
+// Bottom-FC does not depend on the SparseNet and Predict-FC waits for both
+// (Sec. III-A); on one in-order stream that dependency is the launch order.
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "rec_internal.h"
+
+using namespace rec;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Layer {
+    int K = 0, N = 0, Kpad = 0, Npad = 0;
+    const void *W = nullptr;      // bf16 [Npad][Kpad]; fp32 [Kpad] for the one-output layer
+    const float *bias = nullptr;  // fp32 [Npad]
+    bool dot = false;             // last Predict-FC layer: fp32 dot product, not a GEMM
+    bool loaded = false;
+    size_t w_bytes() const { return dot ? sizeof(float) * Kpad : 2 * (size_t)Npad * Kpad; }
+};
+
+}  // namespace
+
+struct rec_model {
+    int T = 0, D = 0, F = 0, dtype = REC_F32;
+    int max_batch = 0;
+    long long max_nnz = 0;
+    std::vector<long long> rows;
+    std::vector<Layer> bottom, top;
+    std::vector<char> table_loaded;
+
+    // workspace carve-up (byte offsets)
+    size_t off_err = 0, off_tables = 0, off_offsets = 0, off_tile_sums = 0, off_pooled = 0,
+           off_x0 = 0, off_act[3] = {0, 0, 0}, ws_bytes = 0;
+    int act_ld = 0;          // widest padded activation row (elements)
+    size_t act_row_bytes = 0;  // bytes of one activation row: bf16 everywhere, fp32 into the dot layer
+    int d_pad = 0;
+    char *ws = nullptr;
+
+    // Stage timing: forward number i records into slot i % slots.
+    std::vector<hipEvent_t> ev;  // slots * (REC_NUM_STAGES + 1)
+    int slots = 0;
+    long long forwards = 0;      // forwards recorded since profiling was switched on
+
+    template <class P>
+    P *at(size_t off) const { return reinterpret_cast<P *>(ws + off); }
+};
+
+namespace {
+
+bool all_loaded(const rec_model *m)
+{
+    for (char c : m->table_loaded)
+        if (!c) return false;
+    for (const Layer &l : m->bottom)
+        if (!l.loaded) return false;
+    for (const Layer &l : m->top)
+        if (!l.loaded) return false;
+    return true;
+}
+
+Layer *find_layer(rec_model *m, int which, int layer)
+{
+    if (which != REC_BOTTOM && which != REC_TOP) return nullptr;
+    std::vector<Layer> &v = which == REC_BOTTOM ? m->bottom : m->top;
+    if (layer < 0 || layer >= (int)v.size()) return nullptr;
+    return &v[layer];
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *rec_status_string(rec_status s)
+{
+    switch (s) {
+    case REC_OK: return "ok";
+    case REC_ERR_ARG: return "bad argument";
+    case REC_ERR_SHAPE: return "layer widths or embedding size do not fit the model";
+    case REC_ERR_STATE: return "call made before what it depends on";
+    case REC_ERR_LENGTHS: return "negative length or sum(lengths) != nnz";
+    case REC_ERR_INDEX_RANGE: return "row id outside its table";
+    case REC_ERR_OVERFLOW: return "count exceeds 32-bit index range";
+    case REC_ERR_DEVICE: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+rec_status rec_create(const rec_config *cfg, rec_model **out)
+{
+    if (!out) return REC_ERR_ARG;
+    *out = nullptr;
+    if (!cfg || !cfg->rows || !cfg->bottom_widths || !cfg->top_widths) return REC_ERR_ARG;
+    if (cfg->num_tables <= 0 || cfg->emb_dim <= 0 || cfg->num_dense <= 0 || cfg->n_bottom <= 0 ||
+        cfg->n_top <= 0 || cfg->max_batch <= 0 || cfg->max_nnz < 0)
+        return REC_ERR_ARG;
+    if (cfg->table_dtype != REC_F32 && cfg->table_dtype != REC_F16) return REC_ERR_ARG;
+
+    const int T = cfg->num_tables, D = cfg->emb_dim;
+    // A row must be 16 * 2^k bytes (k = 0..6) for the 128-bit gather.
+    const long long rowbytes = (long long)D * (cfg->table_dtype == REC_F16 ? 2 : 4);
+    if (rowbytes % 16 != 0) return REC_ERR_SHAPE;
+    const long long lpr = rowbytes / 16;
+    if (lpr > 64 || (lpr & (lpr - 1)) != 0) return REC_ERR_SHAPE;
+
+    for (int t = 0; t < T; ++t) {
+        if (cfg->rows[t] <= 0) return REC_ERR_ARG;
+        if (cfg->rows[t] >= (1ll << 31)) return REC_ERR_OVERFLOW;
+    }
+    if (cfg->max_nnz >= (1ll << 31)) return REC_ERR_OVERFLOW;
+    if ((long long)T * cfg->max_batch >= (1ll << 31)) return REC_ERR_OVERFLOW;
+
+    const long long width = D + (long long)T * (T + 1) / 2;
+    if (width >= (1ll << 24)) return REC_ERR_OVERFLOW;
+    if (cfg->bottom_widths[0] != cfg->num_dense || cfg->bottom_widths[cfg->n_bottom] != D)
+        return REC_ERR_SHAPE;
+    if (cfg->top_widths[0] != width || cfg->top_widths[cfg->n_top] != 1) return REC_ERR_SHAPE;
+    for (int i = 0; i <= cfg->n_bottom; ++i)
+        if (cfg->bottom_widths[i] <= 0 || cfg->bottom_widths[i] >= (1 << 24)) return REC_ERR_SHAPE;
+    for (int i = 0; i <= cfg->n_top; ++i)
+        if (cfg->top_widths[i] <= 0 || cfg->top_widths[i] >= (1 << 24)) return REC_ERR_SHAPE;
+    if (interact_lds_bytes_per_sample(T, D) > 64 * 1024) return REC_ERR_SHAPE;
+
+    rec_model *m = new (std::nothrow) rec_model();
+    if (!m) return REC_ERR_ARG;
+    m->T = T; m->D = D; m->F = cfg->num_dense; m->dtype = cfg->table_dtype;
+    m->max_batch = cfg->max_batch; m->max_nnz = cfg->max_nnz;
+    m->rows.assign(cfg->rows, cfg->rows + T);
+    m->table_loaded.assign(T, 0);
+    m->d_pad = pad_up(D);
+    m->act_ld = pad_up((int)width);
+    auto fill = [&](std::vector<Layer> &v, const int32_t *w, int n) {
+        v.resize(n);
+        for (int i = 0; i < n; ++i) {
+            v[i].K = w[i]; v[i].N = w[i + 1];
+            v[i].Kpad = pad_up(w[i]); v[i].Npad = pad_up(w[i + 1]);
+            if (v[i].Npad > m->act_ld) m->act_ld = v[i].Npad;
+        }
+    };
+    fill(m->bottom, cfg->bottom_widths, cfg->n_bottom);
+    fill(m->top, cfg->top_widths, cfg->n_top);
+    m->top.back().dot = true;
+    m->act_row_bytes = 2 * (size_t)m->act_ld;
+    if (m->top.size() > 1)  // the layer feeding the dot leaves fp32
+        m->act_row_bytes = std::max(m->act_row_bytes, sizeof(float) * m->top[m->top.size() - 2].Npad);
+
+    const size_t nb = (size_t)T * m->max_batch;
+    size_t o = 0;
+    m->off_err = o;       o += align_up(sizeof(ErrRecord));
+    m->off_tables = o;    o += align_up(sizeof(TableDesc) * T);
+    m->off_offsets = o;   o += align_up(sizeof(int32_t) * (nb + 1));
+    m->off_tile_sums = o; o += align_up(sizeof(long long) * ((nb + SCAN_TILE - 1) / SCAN_TILE));
+    m->off_pooled = o;    o += align_up(sizeof(float) * nb * D);
+    m->off_x0 = o;        o += align_up(sizeof(float) * (size_t)m->max_batch * m->d_pad);
+    // act[0] holds the interaction output (kept for inspection); the hidden
+    // activations of both stacks alternate between act[1] and act[2].
+    for (size_t &a : m->off_act) {
+        a = o;
+        o += align_up((size_t)m->max_batch * m->act_row_bytes);
+    }
+    m->ws_bytes = o;
+    *out = m;
+    return REC_OK;
+}
+
+void rec_destroy(rec_model *m)
+{
+    if (!m) return;
+    for (hipEvent_t e : m->ev)
+        if (e) (void)hipEventDestroy(e);
+    delete m;
+}
+
+size_t rec_workspace_bytes(const rec_model *m) { return m ? m->ws_bytes : 0; }
+
+rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *stream)
+{
+    if (!m || !dev_ptr) return REC_ERR_ARG;
+    if (bytes < m->ws_bytes || reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return REC_ERR_ARG;
+    m->ws = static_cast<char *>(dev_ptr);
+    std::fill(m->table_loaded.begin(), m->table_loaded.end(), 0);  // descriptors live in the workspace
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (launch_clear_err(m->at<ErrRecord>(m->off_err), s) != hipSuccess) return REC_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return REC_ERR_DEVICE;
+    return REC_OK;
+}
+
+rec_status rec_load_tables(rec_model *m, int32_t table, const void *dev_rows)
+{
+    if (!m || !dev_rows || table < 0 || table >= m->T) return REC_ERR_ARG;
+    if (reinterpret_cast<uintptr_t>(dev_rows) % 16 != 0) return REC_ERR_ARG;
+    if (!m->ws) return REC_ERR_STATE;
+    TableDesc d{dev_rows, m->rows[table]};
+    if (hipMemcpy(m->at<TableDesc>(m->off_tables) + table, &d, sizeof(d), hipMemcpyHostToDevice) !=
+        hipSuccess)
+        return REC_ERR_DEVICE;
+    m->table_loaded[table] = 1;
+    return REC_OK;
+}
+
+size_t rec_mlp_packed_bytes(const rec_model *m, int32_t which, int32_t layer)
+{
+    if (!m) return 0;
+    const Layer *l = find_layer(const_cast<rec_model *>(m), which, layer);
+    if (!l) return 0;
+    return align_up(l->w_bytes()) + align_up(sizeof(float) * l->Npad);
+}
+
+rec_status rec_load_mlp(rec_model *m, int32_t which, int32_t layer, const float *dev_W,
+                        const float *dev_b, void *dev_packed, void *stream)
+{
+    if (!m || !dev_W || !dev_b || !dev_packed) return REC_ERR_ARG;
+    Layer *l = find_layer(m, which, layer);
+    if (!l) return REC_ERR_ARG;
+    if (reinterpret_cast<uintptr_t>(dev_packed) % ALIGN != 0) return REC_ERR_ARG;
+    char *p = static_cast<char *>(dev_packed);
+    float *bias = reinterpret_cast<float *>(p + align_up(l->w_bytes()));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const hipError_t e = l->dot ? launch_pack_dot(dev_W, dev_b, l->K, l->Kpad, reinterpret_cast<float *>(p), bias, s)
+                                : launch_pack_fc(dev_W, dev_b, l->N, l->K, l->Npad, l->Kpad, p, bias, s);
+    if (e != hipSuccess) return REC_ERR_DEVICE;
+    l->W = p;
+    l->bias = bias;
+    l->loaded = true;
+    return REC_OK;
+}
+
+rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_indices,
+                       const int32_t *dev_lengths, int32_t batch, int64_t nnz, float *dev_logits,
+                       void *stream)
+{
+    if (!m) return REC_ERR_ARG;
+    if (batch < 0 || batch > m->max_batch || nnz < 0 || nnz > m->max_nnz) return REC_ERR_ARG;
+    if (!m->ws || !all_loaded(m)) return REC_ERR_STATE;
+    if (batch == 0) return REC_OK;
+    if (!dev_dense || !dev_lengths || !dev_logits || (nnz > 0 && !dev_indices)) return REC_ERR_ARG;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int B = batch, T = m->T, D = m->D;
+    ErrRecord *err = m->at<ErrRecord>(m->off_err);
+    int32_t *offsets = m->at<int32_t>(m->off_offsets);
+    float *pooled = m->at<float>(m->off_pooled);
+    float *x0 = m->at<float>(m->off_x0);
+    void *act[3] = {m->at<void>(m->off_act[0]), m->at<void>(m->off_act[1]),
+                    m->at<void>(m->off_act[2])};
+    const bool prof = m->slots > 0;
+    hipEvent_t *ev = prof ? &m->ev[(size_t)(m->forwards % m->slots) * (REC_NUM_STAGES + 1)] : nullptr;
+    int stage = 0;
+#define REC_MARK()                                                                      \
+    do {                                                                                \
+        if (prof && hipEventRecord(ev[stage++], s) != hipSuccess) return REC_ERR_DEVICE;   \
+    } while (0)
+#define REC_TRY(call)                                  \
+    do {                                               \
+        if ((call) != hipSuccess) return REC_ERR_DEVICE; \
+    } while (0)
+
+    REC_MARK();
+    // S0
+    REC_TRY(launch_scan(dev_lengths, T * B, nnz, offsets, m->at<long long>(m->off_tile_sums), err, s));
+    REC_MARK();
+    // S1
+    REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
+                        pooled, err, s));
+    REC_MARK();
+    // S2: ReLU after every layer; the last one leaves fp32 for the interaction.
+    {
+        const void *in = dev_dense;
+        int ld_in = m->F;
+        bool in_f32 = true;
+        for (size_t i = 0; i < m->bottom.size(); ++i) {
+            const Layer &l = m->bottom[i];
+            const bool last = i + 1 == m->bottom.size();
+            void *dst = last ? static_cast<void *>(x0) : act[1 + (i & 1)];
+            const int ldc = last ? m->d_pad : m->act_ld;
+            REC_TRY(launch_fc(in, in_f32, ld_in, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true, dst, last,
+                              ldc, s));
+            in = dst; ld_in = ldc; in_f32 = false;
+        }
+    }
+    REC_MARK();
+    // S3 -> act[0], row stride act_ld, zero filled up to it
+    REC_TRY(launch_interact(x0, m->d_pad, pooled, B, T, D, act[0], m->act_ld, s));
+    REC_MARK();
+    // S4: ReLU on all layers but the last.  The last layer is one fp32 dot per
+    // sample; the layer feeding it leaves its output in fp32.
+    {
+        int cur = 0, ld = m->act_ld;
+        bool cur_f32 = false;
+        for (size_t i = 0; i + 1 < m->top.size(); ++i) {
+            const Layer &l = m->top[i];
+            const int nxt = 1 + (int)(i & 1);
+            const bool feeds_dot = i + 2 == m->top.size();
+            const int ldc = feeds_dot ? l.Npad : m->act_ld;
+            REC_TRY(launch_fc(act[cur], false, ld, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true, act[nxt],
+                              feeds_dot, ldc, s));
+            cur = nxt; ld = ldc; cur_f32 = feeds_dot;
+        }
+        const Layer &l = m->top.back();
+        REC_TRY(launch_rowdot(act[cur], cur_f32, ld, B, l.Kpad, static_cast<const float *>(l.W), l.bias,
+                              dev_logits, s));
+    }
+    REC_MARK();
+#undef REC_MARK
+#undef REC_TRY
+    if (prof) ++m->forwards;
+    return REC_OK;
+}
+
+rec_status rec_check(rec_model *m, void *stream, int64_t *first_bad_pos)
+{
+    if (!m) return REC_ERR_ARG;
+    if (!m->ws) return REC_ERR_STATE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ErrRecord h;
+    ErrRecord *d = m->at<ErrRecord>(m->off_err);
+    if (hipStreamSynchronize(s) != hipSuccess) return REC_ERR_DEVICE;
+    if (hipMemcpy(&h, d, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return REC_ERR_DEVICE;
+    if (first_bad_pos) *first_bad_pos = -1;
+    if (h.flags == 0) return REC_OK;
+    if (launch_clear_err(d, s) != hipSuccess) return REC_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return REC_ERR_DEVICE;
+    if (h.flags & (ERR_NEG_LENGTH | ERR_TOTAL_MISMATCH)) {
+        if (first_bad_pos && (h.flags & ERR_NEG_LENGTH)) *first_bad_pos = (int64_t)h.first_bad_len;
+        return REC_ERR_LENGTHS;
+    }
+    if (first_bad_pos) *first_bad_pos = (int64_t)h.first_bad_idx;
+    return REC_ERR_INDEX_RANGE;
+}
+
+rec_status rec_debug_get(rec_model *m, int32_t what, const void **dev_ptr, int64_t *ld_out)
+{
+    if (!m || !dev_ptr) return REC_ERR_ARG;
+    if (!m->ws) return REC_ERR_STATE;
+    int64_t ld = 0;
+    switch (what) {
+    case REC_DBG_OFFSETS: *dev_ptr = m->at<void>(m->off_offsets); ld = 0; break;
+    case REC_DBG_POOLED: *dev_ptr = m->at<void>(m->off_pooled); ld = m->D; break;
+    case REC_DBG_BOTTOM_OUT: *dev_ptr = m->at<void>(m->off_x0); ld = m->d_pad; break;
+    case REC_DBG_INTERACT: *dev_ptr = m->at<void>(m->off_act[0]); ld = m->act_ld; break;
+    default: return REC_ERR_ARG;
+    }
+    if (ld_out) *ld_out = ld;
+    return REC_OK;
+}
+
+rec_status rec_set_profiling(rec_model *m, int32_t slots)
+{
+    if (!m || slots < 0 || slots > 65536) return REC_ERR_ARG;
+    for (hipEvent_t e : m->ev)
+        if (e) (void)hipEventDestroy(e);
+    m->ev.assign((size_t)slots * (REC_NUM_STAGES + 1), nullptr);
+    m->slots = 0;
+    m->forwards = 0;
+    for (hipEvent_t &e : m->ev)
+        if (hipEventCreate(&e) != hipSuccess) return REC_ERR_DEVICE;
+    m->slots = slots;
+    return REC_OK;
+}
+
+rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms)
+{
+    if (!m || !ms) return REC_ERR_ARG;
+    if (m->slots <= 0 || slot < 0 || slot >= m->slots || slot >= m->forwards) return REC_ERR_STATE;
+    hipEvent_t *ev = &m->ev[(size_t)slot * (REC_NUM_STAGES + 1)];
+    if (hipEventSynchronize(ev[REC_NUM_STAGES]) != hipSuccess) return REC_ERR_DEVICE;
+    for (int i = 0; i < REC_NUM_STAGES; ++i)
+        if (hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) return REC_ERR_DEVICE;
+    return REC_OK;
+}
+
+}  // extern "C"

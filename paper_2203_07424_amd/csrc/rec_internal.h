@@ -1,0 +1,72 @@
+// Internal declarations shared by the gfx950 kernels and the C boundary.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rec.h"
+
+namespace rec {
+
+// Device error record (64 bytes, lives at the start of the workspace).
+// Positions are kept with atomicMin, so "none" is all ones.
+struct ErrRecord {
+    unsigned long long first_bad_len;  // smallest position of a negative length
+    unsigned long long first_bad_idx;  // smallest position of an id outside its table
+    unsigned int flags;                // ERR_* bits
+    unsigned int pad[11];
+};
+enum : unsigned int { ERR_NEG_LENGTH = 1u, ERR_TOTAL_MISMATCH = 2u, ERR_INDEX_RANGE = 4u };
+
+struct TableDesc {
+    const void *base;
+    long long rows;
+};
+
+// S0: one scan block covers SCAN_TILE lengths.
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_ITEMS = 8;
+constexpr int SCAN_TILE = SCAN_THREADS * SCAN_ITEMS;
+
+// All activations and packed weights use leading dimensions that are
+// multiples of this many elements.
+constexpr int PAD = 64;
+inline int pad_up(int x) { return (x + PAD - 1) / PAD * PAD; }
+
+hipError_t launch_clear_err(ErrRecord *err, hipStream_t s);
+
+// S0. offsets[k] = min(sum_{j<k} max(len[j], 0), nnz), k = 0..n; block_sums is
+// scratch of ceil(n / SCAN_TILE) int64 entries.
+hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *offsets,
+                       long long *block_sums, ErrRecord *err, hipStream_t s);
+
+// S1. pooled[b][t][:] = sum of the rows of bag (t, b); fp32 accumulation.
+hipError_t launch_pool(const TableDesc *tables, int dtype, int T, int D, int B,
+                       const int32_t *indices, const int32_t *offsets, float *pooled,
+                       ErrRecord *err, hipStream_t s);
+
+// S2 / S4. C[m][n] = act(sum_k A[m][k] * W[n][k] + bias[n]) on bf16 MFMA.
+//   A: bf16 [M][lda] or (a_f32) fp32 [M][lda] with only k < K valid
+//   W: bf16 [Npad][Kpad], bias fp32 [Npad] (zero padded)
+//   C: bf16 [M][ldc] or (out_f32) fp32 [M][ldc], ldc >= Npad
+hipError_t launch_fc(const void *A, bool a_f32, int lda, int M, int K, int Kpad,
+                     const void *W, const float *bias, int Npad, bool relu, void *C,
+                     bool out_f32, int ldc, hipStream_t s);
+
+// Last Predict-FC layer: logits[m] = sum_k A[m][k] * w[k] + bias[0], fp32 arithmetic.
+// A is fp32 [M][lda] (a_f32) or bf16 [M][lda]; w is fp32 [Kpad], zero padded.
+hipError_t launch_rowdot(const void *A, bool a_f32, int lda, int M, int Kpad, const float *w,
+                         const float *bias, float *logits, hipStream_t s);
+hipError_t launch_pack_dot(const float *W, const float *b, int K, int Kpad, float *W_packed,
+                           float *bias_packed, hipStream_t s);
+
+// fp32 [N][K] -> bf16 [Npad][Kpad] (nearest even, zero padded), bias -> fp32 [Npad].
+hipError_t launch_pack_fc(const float *W, const float *b, int N, int K, int Npad, int Kpad,
+                          void *W_packed, float *bias_packed, hipStream_t s);
+
+// S3. out[b] = bf16([x0[b], <v_i, v_j> i > j, 0 ...]) with v = [x0[b], pooled[b][0..T-1]].
+size_t interact_lds_bytes_per_sample(int T, int D);
+hipError_t launch_interact(const float *x0, int ldx0, const float *pooled, int B, int T, int D,
+                           void *out_bf16, int ldo, hipStream_t s);
+
+}  // namespace rec

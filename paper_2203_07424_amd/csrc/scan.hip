@@ -1,0 +1,170 @@
+// S0: pooling lengths -> bag offsets (exclusive scan), staged in LDS.
+//
+// The sparse input gives, per (table, sample), how many ids follow (the pooling
+// factor varies per lookup, Fig. 2(c)); the gather needs where each bag starts.
+// Two passes over at most a few hundred thousand int32: per-tile sums, then
+// per-tile scans that first reduce the sums of the tiles before them.
+#include "rec_internal.h"
+
+namespace rec {
+
+namespace {
+
+__device__ inline long long wave_sum(long long v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;  // valid in lane 0
+}
+
+// Sum over the block, returned to every thread.
+__device__ inline long long block_sum(long long v, long long *s_w)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) s_w[wave] = v;
+    __syncthreads();
+    long long r = 0;
+#pragma unroll
+    for (int w = 0; w < SCAN_THREADS / 64; ++w) r += s_w[w];
+    return r;
+}
+
+__global__ __launch_bounds__(64) void clear_err_kernel(ErrRecord *err)
+{
+    if (threadIdx.x == 0) {
+        err->first_bad_len = ~0ull;
+        err->first_bad_idx = ~0ull;
+        err->flags = 0u;
+    }
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_tile_sums(const int32_t *__restrict__ len,
+                                                               int n, long long *__restrict__ tile_sums)
+{
+    __shared__ long long s_w[SCAN_THREADS / 64];
+    const long long base = (long long)blockIdx.x * SCAN_TILE;
+    long long sum = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        const long long k = base + i * SCAN_THREADS + threadIdx.x;
+        if (k < n) {
+            const int v = len[k];
+            if (v > 0) sum += v;
+        }
+    }
+    sum = block_sum(sum, s_w);
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = sum;
+}
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_tile_offsets(const int32_t *__restrict__ len,
+                                                                  int n, long long nnz,
+                                                                  const long long *__restrict__ tile_sums,
+                                                                  int32_t *__restrict__ offsets,
+                                                                  ErrRecord *err)
+{
+    // One extra word per 32 keeps the 8-per-thread strided reads off one bank.
+    __shared__ int s_tile[SCAN_TILE + SCAN_TILE / 32];
+    __shared__ long long s_w[SCAN_THREADS / 64];
+    __shared__ long long s_wave_excl[SCAN_THREADS / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long base = (long long)blockIdx.x * SCAN_TILE;
+
+    // Sum of all earlier tiles.
+    long long before = 0;
+    for (int j = tid; j < (int)blockIdx.x; j += SCAN_THREADS) before += tile_sums[j];
+    before = block_sum(before, s_w);
+
+    // Coalesced load of this tile; negative lengths count as 0.
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        const int p = i * SCAN_THREADS + tid;
+        const long long k = base + p;
+        int v = 0;
+        if (k < n) v = len[k];
+        if (v < 0) {
+            atomicMin(&err->first_bad_len, (unsigned long long)k);
+            atomicOr(&err->flags, ERR_NEG_LENGTH);
+        }
+        s_tile[p + (p >> 5)] = v > 0 ? v : 0;
+    }
+    __syncthreads();
+
+    // Each thread owns SCAN_ITEMS consecutive entries.
+    int mine[SCAN_ITEMS];
+    long long tsum = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        const int p = tid * SCAN_ITEMS + i;
+        mine[i] = s_tile[p + (p >> 5)];
+        tsum += mine[i];
+    }
+    // Inclusive scan of the thread sums inside the wave, then across waves.
+    long long incl = tsum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const long long up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) s_w[wave] = incl;
+    __syncthreads();
+    if (tid == 0) {
+        long long run = 0;
+#pragma unroll
+        for (int w = 0; w < SCAN_THREADS / 64; ++w) {
+            s_wave_excl[w] = run;
+            run += s_w[w];
+        }
+    }
+    __syncthreads();
+    long long run = before + s_wave_excl[wave] + (incl - tsum);
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        const int p = tid * SCAN_ITEMS + i;
+        // Clamping to nnz keeps every bag inside the ids the caller passed.
+        s_tile[p + (p >> 5)] = (int)(run < nnz ? run : nnz);
+        run += mine[i];
+    }
+    // `run` of the thread owning the last valid entry is the grand total.
+    const long long last = (long long)n - 1 - base;
+    if (last >= 0 && last < SCAN_TILE && tid == (int)(last / SCAN_ITEMS)) {
+        long long total = before + s_wave_excl[wave] + (incl - tsum);
+        for (int i = 0; i <= (int)(last % SCAN_ITEMS); ++i) total += mine[i];
+        offsets[n] = (int)(total < nnz ? total : nnz);
+        if (total != nnz) atomicOr(&err->flags, ERR_TOTAL_MISMATCH);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < SCAN_ITEMS; ++i) {
+        const int p = i * SCAN_THREADS + tid;
+        const long long k = base + p;
+        if (k < n) offsets[k] = s_tile[p + (p >> 5)];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_clear_err(ErrRecord *err, hipStream_t s)
+{
+    hipLaunchKernelGGL(clear_err_kernel, dim3(1), dim3(64), 0, s, err);
+    return hipGetLastError();
+}
+
+hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *offsets,
+                       long long *block_sums, ErrRecord *err, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
+    if (tiles > 1) {
+        hipLaunchKernelGGL(scan_tile_sums, dim3(tiles), dim3(SCAN_THREADS), 0, s, lengths, n,
+                           block_sums);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(scan_tile_offsets, dim3(tiles), dim3(SCAN_THREADS), 0, s, lengths, n, nnz,
+                       block_sums, offsets, err);
+    return hipGetLastError();
+}
+
+}  // namespace rec

@@ -1,0 +1,280 @@
+"""Parity of the HIP path (through the C boundary) against the CPU oracle.
+
+Integer work (offsets, error positions, synthetic table bits) must be bit-exact;
+fp32 pooling within 1e-5 relative; bf16 MLP logits within 2e-2 relative of the
+exact oracle.  Every test prints what it runs before touching the GPU.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rec_oracle as orc
+from paper_2203_07424_amd import synth
+
+import gpu_helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2203_07424_amd import binding as b
+    return b
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def small_mlps(g, F, D, T, hidden_b=(24,), hidden_t=(16,)):
+    def stack(ws):
+        return [((g.standard_normal((ws[i + 1], ws[i])) * ws[i] ** -0.5).astype(np.float32),
+                 (g.standard_normal(ws[i + 1]) * ws[i] ** -0.5).astype(np.float32))
+                for i in range(len(ws) - 1)]
+    return stack((F,) + tuple(hidden_b) + (D,)), stack((D + T * (T + 1) // 2,) + tuple(hidden_t) + (1,))
+
+
+# ------------------------------------------------------------- generator
+@pytest.mark.parametrize("dtype,D,rows", [("f32", 32, 5000), ("f16", 64, 70001), ("f16", 8, 333)])
+def test_device_table_fill_matches_host_generator(binding, dtype, D, rows):
+    say("fill", dtype, D, rows)
+    tdt = torch.float16 if dtype == "f16" else torch.float32
+    tab = torch.empty((rows, D), dtype=tdt, device="cuda")
+    assert binding.rec_synth_fill_table(tab, 2203, 7) == binding.REC_OK
+    torch.cuda.synchronize()
+    want = synth.table_rows(2203, 7, np.arange(rows), D, dtype)
+    bits = np.uint16 if dtype == "f16" else np.uint32
+    got_b, want_b = tab.cpu().numpy().view(bits), want.view(bits)
+    bad = np.argwhere(got_b != want_b)
+    if bad.size:
+        f32 = synth.table_rows(2203, 7, np.arange(rows), D, "f32")
+        ex = [(int(r), int(c), hex(got_b[r, c]), hex(want_b[r, c]), float(f32[r, c]).hex())
+              for r, c in bad[:8]]
+        pytest.fail(f"{len(bad)} of {got_b.size} elements differ, e.g. {ex}")
+
+
+# ------------------------------------------------------------- S0 + S1
+POOL_CASES = [
+    # T, R, D, dtype, B, lo, hi
+    (3, 1000, 32, np.float32, 37, 0, 50),      # 128-byte rows
+    (2, 5000, 64, np.float16, 129, 1, 200),    # 128-byte rows, several id chunks
+    (2, 800, 64, np.float32, 65, 0, 130),      # 256-byte rows
+    (4, 300, 8, np.float16, 50, 0, 70),        # 16-byte rows: 64 rows per load
+    (2, 300, 4, np.float32, 33, 0, 9),         # 16-byte rows
+    (1, 200, 256, np.float32, 9, 0, 17),       # 1 KB rows: one row per load
+    (2, 100, 128, np.float16, 40, 0, 300),     # long bags
+    (5, 2000, 16, np.float32, 1500, 0, 12),    # T*B spans several scan tiles
+]
+
+
+@pytest.mark.parametrize("T,R,D,dtype,B,lo,hi", POOL_CASES)
+def test_offsets_bit_exact_and_pooling_within_tolerance(binding, T, R, D, dtype, B, lo, hi):
+    say("pool case", T, R, D, dtype.__name__, B, lo, hi)
+    g = np.random.default_rng(100 + T * 7 + D)
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(dtype) for _ in range(T)]
+    lens = g.integers(lo, hi + 1, T * B).astype(np.int32)
+    lens[g.integers(0, T * B, 3)] = 0
+    idx = g.integers(0, R, int(lens.sum())).astype(np.int32)
+    bottom, top = small_mlps(g, 5, D, T)
+    m = H.make_model(binding, tabs, bottom, top, B, int(lens.sum()) + 5, 5)
+    batch = synth.Batch(g.standard_normal((B, 5)).astype(np.float32), idx, lens)
+    H.run(m, batch)
+    assert m.check() == (binding.REC_OK, -1)
+    off, rc, _ = orc.offsets(lens)
+    assert np.array_equal(m.debug_offsets().cpu().numpy().astype(np.int64), off)
+    P, A, nbad, _ = orc.pool(tabs, idx, lens, B, want_abs=True)
+    assert nbad == 0
+    got = m.debug_pooled().cpu().numpy()
+    H.check_pooled(got, P, A)
+    # run-to-run determinism: fixed reduction order
+    H.run(m, batch)
+    assert np.array_equal(got, m.debug_pooled().cpu().numpy())
+    m.close()
+
+
+def test_pooling_closed_forms_on_device(binding):
+    say("pool closed forms")
+    g = np.random.default_rng(7)
+    T, R, D, B = 2, 4096, 32, 64
+    lens = g.integers(0, 90, T * B).astype(np.int32)
+    idx = g.integers(0, R, int(lens.sum())).astype(np.int32)
+    bottom, top = small_mlps(g, 4, D, T)
+    dense = g.standard_normal((B, 4)).astype(np.float32)
+    # all-ones tables: pooled value = bag length, exactly
+    m = H.make_model(binding, [np.ones((R, D), np.float32)] * T, bottom, top, B, idx.size, 4)
+    H.run(m, synth.Batch(dense, idx, lens))
+    got = m.debug_pooled().cpu().numpy()
+    assert np.array_equal(got, np.repeat(lens.reshape(T, B).T[:, :, None], D, 2).astype(np.float32))
+    m.close()
+    # row r holds (r mod 2048) + column: sums of small integers are exact in fp32
+    tab = ((np.arange(R) % 2048)[:, None] + np.arange(D)[None, :]).astype(np.float32)
+    m = H.make_model(binding, [tab] * T, bottom, top, B, idx.size, 4)
+    H.run(m, synth.Batch(dense, idx, lens))
+    P, _, _, _ = orc.pool([tab] * T, idx, lens, B)
+    assert np.array_equal(m.debug_pooled().cpu().numpy().astype(np.float64), P)
+    # single-id bags return the row bit for bit (pooling factor 1 = plain lookup)
+    ones = np.ones(T * B, np.int32)
+    idx1 = g.integers(0, R, T * B).astype(np.int32)
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(np.float32) for _ in range(T)]
+    m2 = H.make_model(binding, tabs, bottom, top, B, idx1.size, 4)
+    H.run(m2, synth.Batch(dense, idx1, ones))
+    got = m2.debug_pooled().cpu().numpy()
+    for t in range(T):
+        assert np.array_equal(got[:, t, :], tabs[t][idx1[t * B:(t + 1) * B]])
+    m.close()
+    m2.close()
+
+
+def test_device_faults_are_reported_not_fatal(binding):
+    say("device faults")
+    g = np.random.default_rng(8)
+    T, R, D, B = 2, 50, 32, 6
+    tabs = [g.uniform(-1, 1, (R, D)).astype(np.float32) for _ in range(T)]
+    bottom, top = small_mlps(g, 4, D, T)
+    dense = g.standard_normal((B, 4)).astype(np.float32)
+    lens = np.array([3, 2, 0, 4, 1, 2, 2, 2, 3, 1, 0, 5], dtype=np.int32)
+    idx = g.integers(0, R, int(lens.sum())).astype(np.int32)
+    m = H.make_model(binding, tabs, bottom, top, 8, 100, 4)
+    # ids outside the table: contribute zero, smallest position reported
+    bad = idx.copy()
+    bad[4] = R
+    bad[9] = -3
+    H.run(m, synth.Batch(dense, bad, lens))
+    P, _, nbad, first = orc.pool(tabs, bad, lens, B)
+    assert nbad == 2 and first == 4
+    assert m.check() == (binding.REC_ERR_INDEX_RANGE, 4)
+    assert np.allclose(m.debug_pooled().cpu().numpy(), P, rtol=1e-6, atol=1e-6)
+    assert m.check() == (binding.REC_OK, -1)          # the record was cleared
+    # negative length: counts as zero, position reported
+    neg = lens.copy()
+    neg[3] = -4
+    idx2 = g.integers(0, R, int(np.maximum(neg, 0).sum())).astype(np.int32)
+    H.run(m, synth.Batch(dense, idx2, neg))
+    off, rc, badpos = orc.offsets(neg)
+    assert rc == -1 and badpos == 3
+    assert m.check() == (binding.REC_ERR_LENGTHS, 3)
+    assert np.array_equal(m.debug_offsets().cpu().numpy().astype(np.int64), off)
+    # sum(lengths) != nnz: reported, offsets clamped to nnz so nothing past it is read
+    short = idx[:-4]
+    logits = H.run(m, synth.Batch(dense, short, lens))
+    assert m.check() == (binding.REC_ERR_LENGTHS, -1)
+    assert np.isfinite(logits).all()
+    assert m.debug_offsets().cpu().numpy().max() == short.size
+    # host-checkable faults return at once
+    d = torch.from_numpy(dense).cuda()
+    assert binding.rec_forward(m.handle, d, None, None, B, 5, None) == binding.REC_ERR_ARG
+    assert binding.rec_forward(m.handle, d, None, None, 9, 5, None) == binding.REC_ERR_ARG
+    assert binding.rec_forward(m.handle, None, None, None, 0, 0, None) == binding.REC_OK
+    m.close()
+
+
+# ------------------------------------------------------------- whole forward
+FWD_CASES = [
+    # T, R, D, dtype, B, F, hidden_b, hidden_t
+    (3, 500, 32, np.float32, 70, 13, (40,), (24,)),         # ragged everything
+    (8, 300, 32, np.float16, 1, 5, (64, 32), (64,)),        # a single sample
+    (10, 400, 64, np.float32, 130, 256, (128,), (256, 64)),  # RMC1-like stacks
+    (6, 200, 16, np.float16, 257, 100, (), ()),             # one-layer stacks
+    (12, 150, 64, np.float16, 200, 64, (256, 128), (512, 128)),
+]
+
+
+@pytest.mark.parametrize("T,R,D,dtype,B,F,hb,ht", FWD_CASES)
+def test_forward_every_stage_against_oracle(binding, T, R, D, dtype, B, F, hb, ht):
+    say("forward case", T, R, D, dtype.__name__, B, F, hb, ht)
+    g = np.random.default_rng(200 + T + B)
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(dtype) for _ in range(T)]
+    lens = g.integers(0, 60, T * B).astype(np.int32)
+    idx = g.integers(0, R, int(lens.sum())).astype(np.int32)
+    bottom, top = small_mlps(g, F, D, T, hb, ht)
+    dense = g.standard_normal((B, F)).astype(np.float32)
+    m = H.make_model(binding, tabs, bottom, top, B + 3, idx.size, F)
+    logits = H.run(m, synth.Batch(dense, idx, lens))
+    assert m.check() == (binding.REC_OK, -1)
+    exact = orc.forward(dense, tabs, idx, lens, bottom, top, orc.EXACT)
+    mirror = orc.forward(dense, tabs, idx, lens, bottom, top, orc.BF16_MIRROR)
+    # Bottom-FC output (fp32 on the device)
+    x0 = m.debug_bottom_out().cpu().numpy().astype(np.float64)
+    scale = np.abs(mirror["bottom_out"]).max() + 1e-30
+    assert np.abs(x0 - mirror["bottom_out"]).max() <= 2e-3 * scale
+    assert np.abs(x0 - exact["bottom_out"]).max() <= 2e-2 * scale
+    # interaction (bf16 on the device): compare with the oracle's formula on the
+    # device's own fp32 inputs, within one bf16 rounding
+    z = m.debug_interact().float().cpu().numpy().astype(np.float64)
+    width = D + T * (T + 1) // 2
+    assert not z[:, width:].any()
+    P = m.debug_pooled().cpu().numpy().astype(np.float64)
+    zo = orc.interact(x0, P)
+    assert np.abs(z[:, :width] - zo).max() <= 2.0 ** -8 * np.abs(zo).max() + 1e-30
+    assert (np.abs(z[:, :width] - zo) <= 2.0 ** -8 * np.abs(zo) + 1e-6 * np.abs(zo).max()).all()
+    # logits
+    H.check_logits(logits, exact["logits"], mirror["logits"])
+    m.close()
+
+
+def test_forward_hand_worked_example_is_exact_on_device(binding):
+    import json, os
+    say("hand example")
+    with open(os.path.join(os.path.dirname(__file__), "golden", "hand_example.json")) as f:
+        ex = json.load(f)
+    # D = 2 rows are 8 bytes, below the 16-byte gather unit: widen to D = 4 with zero columns,
+    # which adds zero terms to every dot product.
+    tabs = [np.pad(np.array(t, np.float32), ((0, 0), (0, 2))) for t in ex["tables"]]
+    bW = np.pad(np.array(ex["bottom"][0]["W"], np.float32), ((0, 2), (0, 0)))
+    bb = np.array(ex["bottom"][0]["b"] + [-1.0, -1.0], np.float32)       # ReLU(-1 + ..) = 0 here
+    bW[2:] = 0
+    t0W = np.array(ex["top"][0]["W"], np.float32)
+    t0W = np.concatenate([t0W[:, :2], np.zeros((2, 2), np.float32), t0W[:, 2:]], axis=1)
+    top = [(t0W, np.array(ex["top"][0]["b"], np.float32)),
+           (np.array(ex["top"][1]["W"], np.float32), np.array(ex["top"][1]["b"], np.float32))]
+    m = H.make_model(binding, tabs, [(bW, bb)], top, 2, 5, 2)
+    batch = synth.Batch(np.array(ex["dense"], np.float32), np.array(ex["indices"], np.int32),
+                        np.array(ex["lengths_table_major"], np.int32))
+    logits = H.run(m, batch)
+    assert m.debug_offsets().cpu().numpy().tolist() == ex["expect"]["offsets"]
+    assert m.debug_pooled().cpu().numpy()[:, :, :2].tolist() == ex["expect"]["pooled"]
+    assert logits.tolist() == ex["expect"]["logits"]
+    m.close()
+
+
+def test_tiny_workload_full_batch(binding):
+    w = synth.WORKLOADS["tiny"]
+    say("tiny workload, full batch")
+    m, bottom, top = H.make_workload_model(binding, w)
+    batch = synth.draw_batch(w, 0)
+    logits = H.run(m, batch)
+    assert m.check() == (binding.REC_OK, -1)
+    tabs = [synth.full_table(w, t) for t in range(w.num_tables)]
+    exact = orc.forward(batch.dense, tabs, batch.indices, batch.lengths, bottom, top)
+    mirror = orc.forward(batch.dense, tabs, batch.indices, batch.lengths, bottom, top, orc.BF16_MIRROR)
+    P, A, _, _ = orc.pool(tabs, batch.indices, batch.lengths, w.batch, want_abs=True)
+    H.check_pooled(m.debug_pooled().cpu().numpy(), P, A)
+    H.check_logits(logits, exact["logits"], mirror["logits"])
+    m.close()
+
+
+# ------------------------------------------------------------- full-size workloads
+@pytest.mark.parametrize("name,n_check", [("rmc3", 24), ("rmc1", 24), ("rmc2", 24)])
+def test_full_size_workload_sampled_against_oracle(binding, name, n_check):
+    """The named workload at its full size, in the launch configuration the
+    benchmark times; the oracle recomputes a spread of samples one by one."""
+    w = synth.WORKLOADS[name]
+    say("full-size workload", name)
+    m, bottom, top = H.make_workload_model(binding, w)
+    batch = synth.draw_batch(w, 0)
+    logits = H.run(m, batch)
+    assert m.check() == (binding.REC_OK, -1)
+    off = m.debug_offsets().cpu().numpy()
+    assert off[0] == 0 and off[-1] == batch.nnz
+    assert np.array_equal(np.diff(off.astype(np.int64)), batch.lengths)
+    g = np.random.default_rng(5)
+    pick = np.unique(np.concatenate([[0, 1, w.batch // 2, w.batch - 2, w.batch - 1],
+                                     g.integers(0, w.batch, n_check)]))
+    exact = H.oracle_on_slice(w, batch, pick, bottom, top)
+    mirror = H.oracle_on_slice(w, batch, pick, bottom, top, orc.BF16_MIRROR)
+    pooled = m.debug_pooled()[torch.from_numpy(pick).cuda()].cpu().numpy()
+    H.check_pooled(pooled, exact["pooled"], exact["abs_sum"])
+    H.check_logits(logits[pick], exact["logits"], mirror["logits"])
+    assert np.isfinite(logits).all()
+    m.close()
+    torch.cuda.empty_cache()

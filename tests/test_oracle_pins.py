@@ -342,6 +342,26 @@ def test_forward_steps_compose():
     assert np.array_equal(got["logits"], z[:, 0])
 
 
+def test_forward_bf16_mirror_narrows_matrix_layers_only():
+    # Mirror mode narrows operands of every layer that is a matrix product; the
+    # one-output last layer is a dot product and stays un-narrowed.
+    g = rng(19)
+    dense, tabs, idx, lens, bottom, top = _toy(g, T=3, R=9, D=4, B=4, bottom=(5, 6, 4), top_hidden=(7, 3))
+    got = orc.forward(dense, tabs, idx, lens, bottom, top, orc.BF16_MIRROR)
+    P, _, _, _ = orc.pool(tabs, idx, lens, 4)
+    h = dense.astype(np.float64)
+    for W, b in bottom:
+        h = orc.fc(h, W, b, True, orc.BF16_MIRROR)
+    z = orc.interact(h, P)
+    z = np.vectorize(orc.round_bf16)(z)          # the interaction output is narrowed as well
+    assert np.array_equal(got["interact"], z)
+    for i, (W, b) in enumerate(top):
+        last = i + 1 == len(top)
+        z = orc.fc(z, W, b, not last, orc.EXACT if last else orc.BF16_MIRROR)
+    assert np.array_equal(got["logits"], z[:, 0])
+    assert not np.array_equal(got["logits"], orc.forward(dense, tabs, idx, lens, bottom, top)["logits"])
+
+
 def test_forward_zero_top_weights_give_last_bias():
     g = rng(16)
     dense, tabs, idx, lens, bottom, top = _toy(g)
