@@ -64,6 +64,9 @@ def main() -> int:
     ap.add_argument("--batches", type=int, default=4, help="distinct input batches cycled")
     ap.add_argument("--cpu-samples", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (a kernel of known "
+                         "traffic to scale hardware counters by)")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="do not bracket stages with events inside the timed region")
     args = ap.parse_args()
@@ -114,6 +117,15 @@ def main() -> int:
     def step(i):
         d, idx, lens = dev_batches[i % len(dev_batches)]
         m.forward(d, idx, lens, logits)
+
+    if args.calibration_copy_mib:
+        n = args.calibration_copy_mib << 20
+        src = torch.full((n,), 1, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)

@@ -37,7 +37,8 @@ struct rec_model {
     // workspace carve-up (byte offsets)
     size_t off_err = 0, off_tables = 0, off_offsets = 0, off_tile_sums = 0, off_pooled = 0,
            off_x0 = 0, off_act[3] = {0, 0, 0}, ws_bytes = 0;
-    int act_ld = 0;          // widest padded activation row (elements)
+    int z_ld = 0;            // padded width of the interaction output (act[0])
+    int act_ld = 0;          // widest padded hidden activation row (elements), act[1], act[2]
     size_t act_row_bytes = 0;  // bytes of one activation row: bf16 everywhere, fp32 into the dot layer
     int d_pad = 0;
     char *ws = nullptr;
@@ -133,7 +134,8 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     m->rows.assign(cfg->rows, cfg->rows + T);
     m->table_loaded.assign(T, 0);
     m->d_pad = pad_up(D);
-    m->act_ld = pad_up((int)width);
+    m->z_ld = pad_up((int)width);
+    m->act_ld = PAD;
     auto fill = [&](std::vector<Layer> &v, const int32_t *w, int n) {
         v.resize(n);
         for (int i = 0; i < n; ++i) {
@@ -159,10 +161,9 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     m->off_x0 = o;        o += align_up(sizeof(float) * (size_t)m->max_batch * m->d_pad);
     // act[0] holds the interaction output (kept for inspection); the hidden
     // activations of both stacks alternate between act[1] and act[2].
-    for (size_t &a : m->off_act) {
-        a = o;
-        o += align_up((size_t)m->max_batch * m->act_row_bytes);
-    }
+    m->off_act[0] = o; o += align_up(2 * (size_t)m->max_batch * m->z_ld);
+    m->off_act[1] = o; o += align_up((size_t)m->max_batch * m->act_row_bytes);
+    m->off_act[2] = o; o += align_up((size_t)m->max_batch * m->act_row_bytes);
     m->ws_bytes = o;
     *out = m;
     return REC_OK;
@@ -284,13 +285,13 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         }
     }
     REC_MARK();
-    // S3 -> act[0], row stride act_ld, zero filled up to it
-    REC_TRY(launch_interact(x0, m->d_pad, pooled, B, T, D, act[0], m->act_ld, s));
+    // S3 -> act[0], row stride z_ld, zero filled up to it
+    REC_TRY(launch_interact(x0, m->d_pad, pooled, B, T, D, act[0], m->z_ld, s));
     REC_MARK();
     // S4: ReLU on all layers but the last.  The last layer is one fp32 dot per
     // sample; the layer feeding it leaves its output in fp32.
     {
-        int cur = 0, ld = m->act_ld;
+        int cur = 0, ld = m->z_ld;
         bool cur_f32 = false;
         for (size_t i = 0; i + 1 < m->top.size(); ++i) {
             const Layer &l = m->top[i];
@@ -342,7 +343,7 @@ rec_status rec_debug_get(rec_model *m, int32_t what, const void **dev_ptr, int64
     case REC_DBG_OFFSETS: *dev_ptr = m->at<void>(m->off_offsets); ld = 0; break;
     case REC_DBG_POOLED: *dev_ptr = m->at<void>(m->off_pooled); ld = m->D; break;
     case REC_DBG_BOTTOM_OUT: *dev_ptr = m->at<void>(m->off_x0); ld = m->d_pad; break;
-    case REC_DBG_INTERACT: *dev_ptr = m->at<void>(m->off_act[0]); ld = m->act_ld; break;
+    case REC_DBG_INTERACT: *dev_ptr = m->at<void>(m->off_act[0]); ld = m->z_ld; break;
     default: return REC_ERR_ARG;
     }
     if (ld_out) *ld_out = ld;
