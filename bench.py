@@ -67,6 +67,10 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known "
                          "traffic to scale hardware counters by)")
+    ap.add_argument("--overlap", action="store_true",
+                    help="run Bottom-FC on the library's side stream beside scan and pooling")
+    ap.add_argument("--event-period", type=int, default=10,
+                    help="bracket the stages of every N-th timed step with HIP events")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="do not bracket stages with events inside the timed region")
     args = ap.parse_args()
@@ -101,6 +105,8 @@ def main() -> int:
         m.load_mlp(binding.REC_BOTTOM, i, torch.from_numpy(W), torch.from_numpy(b))
     for i, (W, b) in enumerate(top):
         m.load_mlp(binding.REC_TOP, i, torch.from_numpy(W), torch.from_numpy(b))
+    if args.overlap:
+        m.set_option(binding.REC_OPT_OVERLAP_DENSE, 1)
     torch.cuda.synchronize()
     log(f"model {w.name}: {w.num_tables} x {w.rows} x {w.emb_dim} {w.table_dtype} resident "
         f"({time.time() - t0:.1f} s)")
@@ -134,8 +140,9 @@ def main() -> int:
     assert st == binding.REC_OK, (st, pos)
 
     use_events = not args.no_stage_events
+    n_timed = (args.steps + args.event_period - 1) // args.event_period
     if use_events:
-        m.set_profiling(args.steps)
+        m.set_profiling(n_timed, args.event_period)
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for i in range(args.steps):
@@ -150,17 +157,18 @@ def main() -> int:
     roofline = None
     if use_events:
         acc = np.zeros(binding.REC_NUM_STAGES)
-        for i in range(args.steps):
-            acc += np.array(list(m.stage_ms(i).values()))
-        stage_avg = dict(zip(binding.STAGE_NAMES, (acc / args.steps).tolist()))
+        for j in range(n_timed):
+            acc += np.array(list(m.stage_ms(j).values()))
+        stage_avg = dict(zip(binding.STAGE_NAMES, (acc / n_timed).tolist()))
         m.set_profiling(0)
         pool_bytes = np.mean([algorithmic_pool_bytes(w, host_batches[i % len(host_batches)])
-                              for i in range(args.steps)])
+                              for i in range(0, args.steps, args.event_period)])
         achieved = pool_bytes / (stage_avg["pool"] * 1e-3) / 1e9
         roofline = {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm",
                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                    "bytes_per_launch": float(pool_bytes), "avg_launch_ms": stage_avg["pool"]}
+                    "bytes_per_launch": float(pool_bytes), "avg_launch_ms": stage_avg["pool"],
+                    "launches_timed": n_timed}
 
     cpu = None
     if not args.no_cpu_baseline:

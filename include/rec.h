@@ -112,7 +112,9 @@ REC_API size_t rec_workspace_bytes(const rec_model *m);
 
 /* Hands the model its workspace: dev_ptr is 256-byte aligned device memory of
  * at least rec_workspace_bytes().  Clears the device error record on `stream`
- * and waits for it.  REC_ERR_ARG if too small or misaligned. */
+ * and waits for it; the first call also creates the library's side stream and
+ * its two ordering events on the current device.  REC_ERR_ARG if too small or
+ * misaligned. */
 REC_API rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *stream);
 
 /* Registers table `table`: dev_rows is [rows[table]][emb_dim], row-major, of
@@ -162,12 +164,28 @@ REC_API rec_status rec_check(rec_model *m, void *stream, int64_t *first_bad_pos)
  * ld_out (may be null) receives the row stride in elements where it applies. */
 REC_API rec_status rec_debug_get(rec_model *m, int32_t what, const void **dev_ptr, int64_t *ld_out);
 
-/* Per-stage timing.  rec_set_profiling(m, slots) with slots > 0 makes
- * rec_forward() bracket each stage with HIP events on its stream; forward
- * number i (counted from this call) records into slot i % slots.  slots = 0
- * switches it off.  rec_stage_ms() waits for the events of `slot` and fills
- * ms[REC_NUM_STAGES]; REC_ERR_STATE if that slot has not been recorded. */
-REC_API rec_status rec_set_profiling(rec_model *m, int32_t slots);
+/* Options of rec_set_option(). */
+enum {
+    /* 1: Bottom-FC is enqueued on a stream of the library's own
+     * (default priority), forked from and joined back into the caller's
+     * stream with events, so that it runs beside the offsets scan and the
+     * pooling, on which it does not depend (Sec. III-A; the sparse / dense
+     * split of Sec. IV-A).  0 (default): everything on the caller's stream, in
+     * order; the cross-stream waits cost more than small dense stacks take. */
+    REC_OPT_OVERLAP_DENSE = 0
+};
+REC_API rec_status rec_set_option(rec_model *m, int32_t option, int32_t value);
+
+/* Per-stage timing.  rec_set_profiling(m, slots, period) with slots > 0 makes
+ * rec_forward() bracket each stage with HIP events on its stream for every
+ * period-th forward (counted from this call, starting with the first); the
+ * j-th timed forward records into slot j % slots.  Event records cost a few
+ * microseconds each on the device, hence the period.  slots = 0 switches it
+ * off.  rec_stage_ms() waits for the events of `slot` and fills
+ * ms[REC_NUM_STAGES]; REC_ERR_STATE if that slot has not been recorded.
+ * With REC_OPT_OVERLAP_DENSE the "bottom" stage is only the time the caller's
+ * stream waited for Bottom-FC after pooling had finished. */
+REC_API rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period);
 REC_API rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms);
 
 REC_API const char *rec_status_string(rec_status s);

@@ -28,12 +28,13 @@ REC_ERR_INDEX_RANGE, REC_ERR_OVERFLOW, REC_ERR_DEVICE = 5, 6, 7
 REC_F32, REC_F16 = 0, 1
 REC_BOTTOM, REC_TOP = 0, 1
 REC_DBG_OFFSETS, REC_DBG_POOLED, REC_DBG_BOTTOM_OUT, REC_DBG_INTERACT = 0, 1, 2, 3
+REC_OPT_OVERLAP_DENSE = 0
 REC_NUM_STAGES = 5
 STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top")
 
 EXPORTS = ("rec_create", "rec_destroy", "rec_workspace_bytes", "rec_bind_workspace",
            "rec_load_tables", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_check",
-           "rec_debug_get", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
+           "rec_debug_get", "rec_set_option", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
            "rec_synth_fill_table")
 
 
@@ -67,8 +68,10 @@ _lib.rec_check.restype = C.c_int
 _lib.rec_check.argtypes = [_vp, _vp, C.POINTER(C.c_int64)]
 _lib.rec_debug_get.restype = C.c_int
 _lib.rec_debug_get.argtypes = [_vp, C.c_int32, C.POINTER(_vp), C.POINTER(C.c_int64)]
+_lib.rec_set_option.restype = C.c_int
+_lib.rec_set_option.argtypes = [_vp, C.c_int32, C.c_int32]
 _lib.rec_set_profiling.restype = C.c_int
-_lib.rec_set_profiling.argtypes = [_vp, C.c_int32]
+_lib.rec_set_profiling.argtypes = [_vp, C.c_int32, C.c_int32]
 _lib.rec_stage_ms.restype = C.c_int
 _lib.rec_stage_ms.argtypes = [_vp, C.c_int32, C.POINTER(C.c_float)]
 _lib.rec_status_string.restype = C.c_char_p
@@ -156,8 +159,12 @@ def rec_debug_get(m: int, what: int) -> Tuple[int, Optional[int], int]:
     return st, p.value, int(ld.value)
 
 
-def rec_set_profiling(m: int, slots: int) -> int:
-    return _lib.rec_set_profiling(m, int(slots))
+def rec_set_option(m: int, option: int, value: int) -> int:
+    return _lib.rec_set_option(m, int(option), int(value))
+
+
+def rec_set_profiling(m: int, slots: int, period: int = 1) -> int:
+    return _lib.rec_set_profiling(m, int(slots), int(period))
 
 
 def rec_stage_ms(m: int, slot: int = 0) -> Tuple[int, List[float]]:
@@ -239,8 +246,11 @@ class RecModel:
     def check(self) -> Tuple[int, int]:
         return rec_check(self.handle)
 
-    def set_profiling(self, slots: int) -> None:
-        self._ok(rec_set_profiling(self.handle, slots), "rec_set_profiling")
+    def set_option(self, option: int, value: int) -> None:
+        self._ok(rec_set_option(self.handle, option, value), "rec_set_option")
+
+    def set_profiling(self, slots: int, period: int = 1) -> None:
+        self._ok(rec_set_profiling(self.handle, slots, period), "rec_set_profiling")
 
     def stage_ms(self, slot: int = 0) -> dict:
         st, ms = rec_stage_ms(self.handle, slot)

@@ -29,48 +29,78 @@ constexpr int BK = 64;            // k extent of one staged tile
 constexpr int LDS_LD = BK + 8;    // row stride in LDS (elements); 144 B keeps 16-byte reads conflict-free
 constexpr int FC_THREADS = 256;
 
-// 8 consecutive k of one activation row, as bf16.
+// 8 consecutive k of one activation row as fetched: raw fp32 (narrowed only when
+// it is stored to LDS, so that the load stays in flight) or bf16.
 template <bool A_F32>
-__device__ inline bf16x8 load_a_chunk(const void *A, long long row, int lda, int k, int K, bool vec_ok)
-{
-    bf16x8 out;
-    if (A_F32) {
-        const float *p = static_cast<const float *>(A) + row * lda + k;
-        if (vec_ok && k + 8 <= K) {
-            const f32x4 lo = *reinterpret_cast<const f32x4 *>(p);
-            const f32x4 hi = *reinterpret_cast<const f32x4 *>(p + 4);
+struct AChunk;
+template <>
+struct AChunk<true> {
+    f32x4 lo, hi;
+    __device__ inline bf16x8 narrow() const
+    {
+        bf16x8 o;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                out[i] = (__bf16)lo[i];
-                out[i + 4] = (__bf16)hi[i];
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) out[i] = (__bf16)((k + i < K) ? p[i] : 0.0f);
+        for (int i = 0; i < 4; ++i) {
+            o[i] = (__bf16)lo[i];
+            o[i + 4] = (__bf16)hi[i];
         }
-    } else {
-        // bf16 activations live in buffers whose columns up to lda are valid (zero padded).
-        out = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(A) + row * lda + k);
+        return o;
     }
-    return out;
+};
+template <>
+struct AChunk<false> {
+    bf16x8 v;
+    __device__ inline bf16x8 narrow() const { return v; }
+};
+
+__device__ inline void load_a_chunk(AChunk<true> &c, const void *A, long long row, int lda, int k,
+                                    int K, bool vec_ok)
+{
+    const float *p = static_cast<const float *>(A) + row * lda + k;
+    if (vec_ok && k + 8 <= K) {
+        c.lo = *reinterpret_cast<const f32x4 *>(p);
+        c.hi = *reinterpret_cast<const f32x4 *>(p + 4);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            c.lo[i] = (k + i < K) ? p[i] : 0.0f;
+            c.hi[i] = (k + 4 + i < K) ? p[4 + i] : 0.0f;
+        }
+    }
 }
 
-template <int BM, int BN, bool A_F32, bool OUT_F32>
+__device__ inline void load_a_chunk(AChunk<false> &c, const void *A, long long row, int lda, int k,
+                                    int, bool)
+{
+    // bf16 activations live in buffers whose columns up to lda are valid (zero padded).
+    c.v = *reinterpret_cast<const bf16x8 *>(static_cast<const __bf16 *>(A) + row * lda + k);
+}
+
+// BM x BN block tile, 4 waves laid out WAVES_M x (4 / WAVES_M), P k-tiles of
+// global loads in flight.  FUSE_DOT (needs BN == Npad): instead of storing C,
+// the epilogue contracts act(C) with a weight vector - the one-output last
+// layer - and writes one fp32 logit per row.
+template <int BM, int BN, int WAVES_M, int P, bool A_F32, bool OUT_F32, bool FUSE_DOT>
 __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__ A, int lda, int M,
                                                         int K, int Kpad,
                                                         const __bf16 *__restrict__ W,
                                                         const float *__restrict__ bias, int relu,
-                                                        void *__restrict__ C, int ldc, int vec_ok)
+                                                        void *__restrict__ C, int ldc, int vec_ok,
+                                                        const float *__restrict__ dot_w,
+                                                        const float *__restrict__ dot_bias,
+                                                        float *__restrict__ dot_out)
 {
-    constexpr int WM = BM / 2, WN = BN / 2;     // per-wave tile (2 x 2 waves)
-    constexpr int TM = WM / 32, TN = WN / 32;   // 32 x 32 MFMA tiles per wave
+    constexpr int WAVES_N = 4 / WAVES_M;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // per-wave tile
+    constexpr int TM = WM / 32, TN = WN / 32;            // 32 x 32 MFMA tiles per wave
     constexpr int A_LOADS = BM / 32, W_LOADS = BN / 32;
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be whole MFMA tiles");
 
     __shared__ __attribute__((aligned(16))) __bf16 sA[BM * LDS_LD];
     __shared__ __attribute__((aligned(16))) __bf16 sW[BN * LDS_LD];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
 
     // Staging role: 8 threads cover the 64 k of one row, 32 rows per pass.
@@ -84,55 +114,70 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    bf16x8 ra[A_LOADS], rw[W_LOADS];
-    auto fetch = [&](int kt) {
-        const int k = kt * BK + ld_chunk * 8;
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            int row = m0 + ld_row + 32 * i;
-            row = row < M ? row : M - 1;  // rows past M are computed and dropped
-            ra[i] = load_a_chunk<A_F32>(A, row, lda, k, K, vec_ok);
-        }
-#pragma unroll
-        for (int i = 0; i < W_LOADS; ++i) {
-            const long long row = n0 + ld_row + 32 * i;
-            rw[i] = *reinterpret_cast<const bf16x8 *>(W + row * Kpad + k);
-        }
-    };
-
+    AChunk<A_F32> ra[P][A_LOADS];
+    bf16x8 rw[P][W_LOADS];
     const int nk = Kpad / BK;
-    fetch(0);
-    for (int kt = 0; kt < nk; ++kt) {
-        __syncthreads();
+
+#define REC_FC_FETCH(kt, slot)                                                              \
+    do {                                                                                    \
+        const int k_ = (kt) * BK + ld_chunk * 8;                                            \
+        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i) {                               \
+            int row_ = m0 + ld_row + 32 * i;                                                \
+            row_ = row_ < M ? row_ : M - 1; /* rows past M are computed and dropped */      \
+            load_a_chunk(ra[slot][i], A, row_, lda, k_, K, vec_ok);                         \
+        }                                                                                   \
+        _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i) {                               \
+            const long long row_ = n0 + ld_row + 32 * i;                                    \
+            rw[slot][i] = *reinterpret_cast<const bf16x8 *>(W + row_ * Kpad + k_);          \
+        }                                                                                   \
+    } while (0)
+
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i)
-            *reinterpret_cast<bf16x8 *>(&sA[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = ra[i];
+    for (int p = 0; p < P; ++p)
+        if (p < nk) REC_FC_FETCH(p, p);
+
+    for (int kt0 = 0; kt0 < nk; kt0 += P) {
 #pragma unroll
-        for (int i = 0; i < W_LOADS; ++i)
-            *reinterpret_cast<bf16x8 *>(&sW[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = rw[i];
-        __syncthreads();
-        if (kt + 1 < nk) fetch(kt + 1);
+        for (int u = 0; u < P; ++u) {
+            const int kt = kt0 + u;
+            if (kt < nk) {
+                __syncthreads();
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int kofs = kk * 16 + (lane >> 5) * 8;
-            bf16x8 fw[TN], fa[TM];
+                for (int i = 0; i < A_LOADS; ++i)
+                    *reinterpret_cast<bf16x8 *>(&sA[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) =
+                        ra[u][i].narrow();
 #pragma unroll
-            for (int i = 0; i < TN; ++i)
-                fw[i] = *reinterpret_cast<const bf16x8 *>(
-                    &sW[(wn * WN + i * 32 + (lane & 31)) * LDS_LD + kofs]);
+                for (int i = 0; i < W_LOADS; ++i)
+                    *reinterpret_cast<bf16x8 *>(&sW[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = rw[u][i];
+                __syncthreads();
+                if (kt + P < nk) REC_FC_FETCH(kt + P, u);
 #pragma unroll
-            for (int j = 0; j < TM; ++j)
-                fa[j] = *reinterpret_cast<const bf16x8 *>(
-                    &sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]);
+                for (int kk = 0; kk < BK / 16; ++kk) {
+                    const int kofs = kk * 16 + (lane >> 5) * 8;
+                    bf16x8 fw[TN], fa[TM];
 #pragma unroll
-            for (int i = 0; i < TN; ++i)
+                    for (int i = 0; i < TN; ++i)
+                        fw[i] = *reinterpret_cast<const bf16x8 *>(
+                            &sW[(wn * WN + i * 32 + (lane & 31)) * LDS_LD + kofs]);
 #pragma unroll
-                for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < TM; ++j)
+                        fa[j] = *reinterpret_cast<const bf16x8 *>(
+                            &sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]);
+#pragma unroll
+                    for (int i = 0; i < TN; ++i)
+#pragma unroll
+                        for (int j = 0; j < TM; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+                }
+            }
         }
     }
+#undef REC_FC_FETCH
 
     // acc[i][j][r]: feature n = 8 * (r / 4) + 4 * (lane / 32) + r % 4, sample m = lane % 32.
+    float dot[TM];
+#pragma unroll
+    for (int j = 0; j < TM; ++j) dot[j] = 0.0f;
 #pragma unroll
     for (int i = 0; i < TN; ++i) {
 #pragma unroll
@@ -148,7 +193,11 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
                     float x = acc[i][j][4 * q + r] + bv[r];
                     v[r] = (relu && x < 0.0f) ? 0.0f : x;
                 }
-                if (m < M) {
+                if (FUSE_DOT) {
+                    const f32x4 wv = *reinterpret_cast<const f32x4 *>(dot_w + n);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) dot[j] += v[r] * wv[r];
+                } else if (m < M) {
                     if (OUT_F32) {
                         *reinterpret_cast<f32x4 *>(static_cast<float *>(C) + (long long)m * ldc + n) = v;
                     } else {
@@ -161,26 +210,53 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
             }
         }
     }
+    if (FUSE_DOT) {
+        // Lanes l and l ^ 32 hold the two halves of a sample's features in this
+        // wave; the WAVES_N waves of a row of waves hold the rest.
+        float *red = reinterpret_cast<float *>(sA);  // [WAVES_N][BM], the tiles are done with
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const float d = dot[j] + __shfl_xor(dot[j], 32, 64);
+            if (lane < 32) red[wn * BM + wm * WM + j * 32 + lane] = d;
+        }
+        __syncthreads();
+        if (tid < BM && m0 + tid < M) {
+            float d = dot_bias[0];
+#pragma unroll
+            for (int w = 0; w < WAVES_N; ++w) d += red[w * BM + tid];
+            dot_out[m0 + tid] = d;
+        }
+    }
 }
 
-template <int BM, int BN>
-hipError_t launch_tile(const void *A, bool a_f32, int lda, int M, int K, int Kpad, const void *W,
-                       const float *bias, int Npad, bool relu, void *C, bool out_f32, int ldc,
-                       hipStream_t s)
+struct FcArgs {
+    const void *A; bool a_f32; int lda, M, K, Kpad;
+    const void *W; const float *bias; int Npad; bool relu;
+    void *C; bool out_f32; int ldc;
+    const float *dot_w, *dot_bias; float *dot_out;  // non-null dot_out: fused one-output layer
+};
+
+template <int BM, int BN, int WAVES_M, int P>
+hipError_t launch_tile(const FcArgs &a, hipStream_t s)
 {
-    const dim3 grid(Npad / BN, (M + BM - 1) / BM), block(FC_THREADS);
-    const __bf16 *Wb = static_cast<const __bf16 *>(W);
+    const dim3 grid(a.Npad / BN, (a.M + BM - 1) / BM), block(FC_THREADS);
+    const __bf16 *Wb = static_cast<const __bf16 *>(a.W);
     // 16-byte loads of fp32 rows need lda % 4 == 0 and an aligned base.
-    const int vec_ok = a_f32 && (lda % 4 == 0) && (reinterpret_cast<uintptr_t>(A) % 16 == 0);
-    const int r = relu ? 1 : 0;
-    if (a_f32 && out_f32)
-        hipLaunchKernelGGL((fc_kernel<BM, BN, true, true>), grid, block, 0, s, A, lda, M, K, Kpad, Wb, bias, r, C, ldc, vec_ok);
-    else if (a_f32)
-        hipLaunchKernelGGL((fc_kernel<BM, BN, true, false>), grid, block, 0, s, A, lda, M, K, Kpad, Wb, bias, r, C, ldc, vec_ok);
-    else if (out_f32)
-        hipLaunchKernelGGL((fc_kernel<BM, BN, false, true>), grid, block, 0, s, A, lda, M, K, Kpad, Wb, bias, r, C, ldc, vec_ok);
-    else
-        hipLaunchKernelGGL((fc_kernel<BM, BN, false, false>), grid, block, 0, s, A, lda, M, K, Kpad, Wb, bias, r, C, ldc, vec_ok);
+    const int vec_ok = a.a_f32 && (a.lda % 4 == 0) && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0);
+    const int r = a.relu ? 1 : 0;
+#define REC_FC_LAUNCH(AF, OF, FD)                                                                  \
+    hipLaunchKernelGGL((fc_kernel<BM, BN, WAVES_M, P, AF, OF, FD>), grid, block, 0, s, a.A, a.lda, \
+                       a.M, a.K, a.Kpad, Wb, a.bias, r, a.C, a.ldc, vec_ok, a.dot_w, a.dot_bias,   \
+                       a.dot_out)
+    if (a.dot_out) {
+        if (a.a_f32) REC_FC_LAUNCH(true, false, true);
+        else REC_FC_LAUNCH(false, false, true);
+    } else if (a.a_f32 && a.out_f32) REC_FC_LAUNCH(true, true, false);
+    else if (a.a_f32) REC_FC_LAUNCH(true, false, false);
+    else if (a.out_f32) REC_FC_LAUNCH(false, true, false);
+    else REC_FC_LAUNCH(false, false, false);
+#undef REC_FC_LAUNCH
     return hipGetLastError();
 }
 
@@ -250,17 +326,27 @@ __global__ __launch_bounds__(256) void pack_fc_kernel(const float *__restrict__ 
 
 }  // namespace
 
+bool fc_can_fuse_dot(int Npad) { return Npad == 64 || Npad == 128; }
+
 hipError_t launch_fc(const void *A, bool a_f32, int lda, int M, int K, int Kpad, const void *W,
                      const float *bias, int Npad, bool relu, void *C, bool out_f32, int ldc,
-                     hipStream_t s)
+                     const float *dot_w, const float *dot_bias, float *dot_out, hipStream_t s)
 {
     if (M <= 0) return hipSuccess;
     if (Kpad % BK != 0 || Npad % 64 != 0) return hipErrorInvalidValue;
+    const FcArgs a{A, a_f32, lda, M, K, Kpad, W, bias, Npad, relu, C, out_f32, ldc, dot_w, dot_bias, dot_out};
+    if (dot_out) {
+        // The block must own whole rows.
+        if (Npad == 128) return launch_tile<32, 128, 1, 4>(a, s);
+        if (Npad == 64) return launch_tile<64, 64, 2, 4>(a, s);
+        return hipErrorInvalidValue;
+    }
     // Large tiles only where they still give every compute unit a block.
     const long long big_blocks = (long long)(Npad / 128) * ((M + 127) / 128);
-    if (Npad % 128 == 0 && big_blocks >= 256)
-        return launch_tile<128, 128>(A, a_f32, lda, M, K, Kpad, W, bias, Npad, relu, C, out_f32, ldc, s);
-    return launch_tile<64, 64>(A, a_f32, lda, M, K, Kpad, W, bias, Npad, relu, C, out_f32, ldc, s);
+    if (Npad % 128 == 0 && big_blocks >= 256) return launch_tile<128, 128, 2, 2>(a, s);
+    const long long mid_blocks = (long long)(Npad / 64) * ((M + 63) / 64);
+    if (Npad % 128 == 0 && mid_blocks < 256) return launch_tile<32, 128, 1, 4>(a, s);
+    return launch_tile<64, 64, 2, 4>(a, s);
 }
 
 hipError_t launch_rowdot(const void *A, bool a_f32, int lda, int M, int Kpad, const float *w,

@@ -43,10 +43,15 @@ struct rec_model {
     int d_pad = 0;
     char *ws = nullptr;
 
+    // Bottom-FC runs on a stream of the library's own, beside scan and pooling.
+    bool overlap_dense = false;
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+
     // Stage timing: forward number i records into slot i % slots.
     std::vector<hipEvent_t> ev;  // slots * (REC_NUM_STAGES + 1)
-    int slots = 0;
-    long long forwards = 0;      // forwards recorded since profiling was switched on
+    int slots = 0, period = 1;
+    long long forwards = 0;      // forwards seen since profiling was switched on
 
     template <class P>
     P *at(size_t off) const { return reinterpret_cast<P *>(ws + off); }
@@ -174,6 +179,9 @@ void rec_destroy(rec_model *m)
     if (!m) return;
     for (hipEvent_t e : m->ev)
         if (e) (void)hipEventDestroy(e);
+    if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
+    if (m->ev_join) (void)hipEventDestroy(m->ev_join);
+    if (m->side) (void)hipStreamDestroy(m->side);
     delete m;
 }
 
@@ -183,6 +191,13 @@ rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *s
 {
     if (!m || !dev_ptr) return REC_ERR_ARG;
     if (bytes < m->ws_bytes || reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return REC_ERR_ARG;
+    if (!m->side) {
+        // Default priority; the two events only order work, they carry no timing.
+        if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess)
+            return REC_ERR_DEVICE;
+    }
     m->ws = static_cast<char *>(dev_ptr);
     std::fill(m->table_loaded.begin(), m->table_loaded.end(), 0);  // descriptors live in the workspace
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -249,8 +264,11 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
     float *x0 = m->at<float>(m->off_x0);
     void *act[3] = {m->at<void>(m->off_act[0]), m->at<void>(m->off_act[1]),
                     m->at<void>(m->off_act[2])};
-    const bool prof = m->slots > 0;
-    hipEvent_t *ev = prof ? &m->ev[(size_t)(m->forwards % m->slots) * (REC_NUM_STAGES + 1)] : nullptr;
+    // Forward number i is timed when i is a multiple of the period; it is the
+    // (i / period)-th timed one.
+    const bool prof = m->slots > 0 && m->forwards % m->period == 0;
+    hipEvent_t *ev = prof ? &m->ev[(size_t)((m->forwards / m->period) % m->slots) * (REC_NUM_STAGES + 1)]
+                          : nullptr;
     int stage = 0;
 #define REC_MARK()                                                                      \
     do {                                                                                \
@@ -261,16 +279,12 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         if ((call) != hipSuccess) return REC_ERR_DEVICE; \
     } while (0)
 
-    REC_MARK();
-    // S0
-    REC_TRY(launch_scan(dev_lengths, T * B, nnz, offsets, m->at<long long>(m->off_tile_sums), err, s));
-    REC_MARK();
-    // S1
-    REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
-                        pooled, err, s));
-    REC_MARK();
-    // S2: ReLU after every layer; the last one leaves fp32 for the interaction.
-    {
+    // S2 does not depend on S0/S1: with overlap it is enqueued on the side
+    // stream, forked from and joined back into the caller's stream.
+    const bool overlap = m->overlap_dense;
+    hipStream_t sd = overlap ? m->side : s;
+    auto bottom_fc = [&]() -> hipError_t {
+        // ReLU after every layer; the last one leaves fp32 for the interaction.
         const void *in = dev_dense;
         int ld_in = m->F;
         bool in_f32 = true;
@@ -279,37 +293,67 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
             const bool last = i + 1 == m->bottom.size();
             void *dst = last ? static_cast<void *>(x0) : act[1 + (i & 1)];
             const int ldc = last ? m->d_pad : m->act_ld;
-            REC_TRY(launch_fc(in, in_f32, ld_in, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true, dst, last,
-                              ldc, s));
+            const hipError_t e = launch_fc(in, in_f32, ld_in, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true,
+                                           dst, last, ldc, nullptr, nullptr, nullptr, sd);
+            if (e != hipSuccess) return e;
             in = dst; ld_in = ldc; in_f32 = false;
         }
+        return hipSuccess;
+    };
+
+    REC_MARK();
+    if (overlap) {
+        REC_TRY(hipEventRecord(m->ev_fork, s));
+        REC_TRY(hipStreamWaitEvent(sd, m->ev_fork, 0));
+        REC_TRY(bottom_fc());
+        REC_TRY(hipEventRecord(m->ev_join, sd));
     }
+    // S0
+    REC_TRY(launch_scan(dev_lengths, T * B, nnz, offsets, m->at<long long>(m->off_tile_sums), err, s));
+    REC_MARK();
+    // S1
+    REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
+                        pooled, err, s));
+    REC_MARK();
+    // S2, or the wait for it (the "bottom" stage then times only what pooling did not hide)
+    if (overlap)
+        REC_TRY(hipStreamWaitEvent(s, m->ev_join, 0));
+    else
+        REC_TRY(bottom_fc());
     REC_MARK();
     // S3 -> act[0], row stride z_ld, zero filled up to it
     REC_TRY(launch_interact(x0, m->d_pad, pooled, B, T, D, act[0], m->z_ld, s));
     REC_MARK();
     // S4: ReLU on all layers but the last.  The last layer is one fp32 dot per
-    // sample; the layer feeding it leaves its output in fp32.
+    // sample: folded into the epilogue of the layer before it when that layer's
+    // block tile spans whole rows, else that layer leaves fp32 for a dot kernel.
     {
         int cur = 0, ld = m->z_ld;
-        bool cur_f32 = false;
+        bool cur_f32 = false, done = false;
+        const Layer &dotl = m->top.back();
         for (size_t i = 0; i + 1 < m->top.size(); ++i) {
             const Layer &l = m->top[i];
             const int nxt = 1 + (int)(i & 1);
             const bool feeds_dot = i + 2 == m->top.size();
+            if (feeds_dot && fc_can_fuse_dot(l.Npad)) {
+                REC_TRY(launch_fc(act[cur], false, ld, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true, nullptr,
+                                  false, 0, static_cast<const float *>(dotl.W), dotl.bias, dev_logits, s));
+                done = true;
+                break;
+            }
             const int ldc = feeds_dot ? l.Npad : m->act_ld;
             REC_TRY(launch_fc(act[cur], false, ld, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true, act[nxt],
-                              feeds_dot, ldc, s));
+                              feeds_dot, ldc, nullptr, nullptr, nullptr, s));
             cur = nxt; ld = ldc; cur_f32 = feeds_dot;
         }
-        const Layer &l = m->top.back();
-        REC_TRY(launch_rowdot(act[cur], cur_f32, ld, B, l.Kpad, static_cast<const float *>(l.W), l.bias,
-                              dev_logits, s));
+        if (!done)
+            REC_TRY(launch_rowdot(act[cur], cur_f32, ld, B, dotl.Kpad, static_cast<const float *>(dotl.W),
+                                  dotl.bias, dev_logits, s));
     }
     REC_MARK();
 #undef REC_MARK
 #undef REC_TRY
-    if (prof) ++m->forwards;
+    if (m->slots > 0) ++m->forwards;
     return REC_OK;
 }
 
@@ -350,9 +394,18 @@ rec_status rec_debug_get(rec_model *m, int32_t what, const void **dev_ptr, int64
     return REC_OK;
 }
 
-rec_status rec_set_profiling(rec_model *m, int32_t slots)
+rec_status rec_set_option(rec_model *m, int32_t option, int32_t value)
 {
-    if (!m || slots < 0 || slots > 65536) return REC_ERR_ARG;
+    if (!m) return REC_ERR_ARG;
+    switch (option) {
+    case REC_OPT_OVERLAP_DENSE: m->overlap_dense = value != 0; return REC_OK;
+    default: return REC_ERR_ARG;
+    }
+}
+
+rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period)
+{
+    if (!m || slots < 0 || slots > 65536 || (slots > 0 && period < 1)) return REC_ERR_ARG;
     for (hipEvent_t e : m->ev)
         if (e) (void)hipEventDestroy(e);
     m->ev.assign((size_t)slots * (REC_NUM_STAGES + 1), nullptr);
@@ -361,13 +414,15 @@ rec_status rec_set_profiling(rec_model *m, int32_t slots)
     for (hipEvent_t &e : m->ev)
         if (hipEventCreate(&e) != hipSuccess) return REC_ERR_DEVICE;
     m->slots = slots;
+    m->period = slots > 0 ? period : 1;
     return REC_OK;
 }
 
 rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms)
 {
     if (!m || !ms) return REC_ERR_ARG;
-    if (m->slots <= 0 || slot < 0 || slot >= m->slots || slot >= m->forwards) return REC_ERR_STATE;
+    const long long timed = (m->forwards + m->period - 1) / m->period;  // timed forwards so far
+    if (m->slots <= 0 || slot < 0 || slot >= m->slots || slot >= timed) return REC_ERR_STATE;
     hipEvent_t *ev = &m->ev[(size_t)slot * (REC_NUM_STAGES + 1)];
     if (hipEventSynchronize(ev[REC_NUM_STAGES]) != hipSuccess) return REC_ERR_DEVICE;
     for (int i = 0; i < REC_NUM_STAGES; ++i)

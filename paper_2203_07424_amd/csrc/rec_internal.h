@@ -49,9 +49,14 @@ hipError_t launch_pool(const TableDesc *tables, int dtype, int T, int D, int B,
 //   A: bf16 [M][lda] or (a_f32) fp32 [M][lda] with only k < K valid
 //   W: bf16 [Npad][Kpad], bias fp32 [Npad] (zero padded)
 //   C: bf16 [M][ldc] or (out_f32) fp32 [M][ldc], ldc >= Npad
+// With dot_out != null (allowed when fc_can_fuse_dot(Npad)) C is not stored;
+// instead dot_out[m] = sum_n act(C[m][n]) * dot_w[n] + dot_bias[0], the
+// one-output layer that follows, in fp32.
+bool fc_can_fuse_dot(int Npad);
 hipError_t launch_fc(const void *A, bool a_f32, int lda, int M, int K, int Kpad,
                      const void *W, const float *bias, int Npad, bool relu, void *C,
-                     bool out_f32, int ldc, hipStream_t s);
+                     bool out_f32, int ldc, const float *dot_w, const float *dot_bias,
+                     float *dot_out, hipStream_t s);
 
 // Last Predict-FC layer: logits[m] = sum_k A[m][k] * w[k] + bias[0], fp32 arithmetic.
 // A is fp32 [M][lda] (a_f32) or bf16 [M][lda]; w is fp32 [Kpad], zero padded.

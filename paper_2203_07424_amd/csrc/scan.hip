@@ -3,7 +3,9 @@
 // The sparse input gives, per (table, sample), how many ids follow (the pooling
 // factor varies per lookup, Fig. 2(c)); the gather needs where each bag starts.
 // Two passes over at most a few hundred thousand int32: per-tile sums, then
-// per-tile scans that first reduce the sums of the tiles before them.
+// per-tile scans in LDS that first reduce the sums of the tiles before them.
+// (One launch in which every block re-reads the earlier lengths itself was
+// measured 5x slower: a single block pulls only tens of GB/s.)
 #include "rec_internal.h"
 
 namespace rec {
@@ -156,6 +158,7 @@ hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *of
 {
     if (n <= 0) return hipSuccess;
     const int tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
+    const long long *sums = block_sums;  // never read by the single tile of a small input
     if (tiles > 1) {
         hipLaunchKernelGGL(scan_tile_sums, dim3(tiles), dim3(SCAN_THREADS), 0, s, lengths, n,
                            block_sums);
@@ -163,7 +166,7 @@ hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *of
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(scan_tile_offsets, dim3(tiles), dim3(SCAN_THREADS), 0, s, lengths, n, nnz,
-                       block_sums, offsets, err);
+                       sums, offsets, err);
     return hipGetLastError();
 }
 

@@ -64,6 +64,7 @@ POOL_CASES = [
     (1, 200, 256, np.float32, 9, 0, 17),       # 1 KB rows: one row per load
     (2, 100, 128, np.float16, 40, 0, 300),     # long bags
     (5, 2000, 16, np.float32, 1500, 0, 12),    # T*B spans several scan tiles
+    (3, 500, 4, np.float32, 100_000, 0, 3),    # 300,000 bags: the two-pass scan
 ]
 
 
@@ -209,6 +210,43 @@ def test_forward_every_stage_against_oracle(binding, T, R, D, dtype, B, F, hb, h
     assert (np.abs(z[:, :width] - zo) <= 2.0 ** -8 * np.abs(zo) + 1e-6 * np.abs(zo).max()).all()
     # logits
     H.check_logits(logits, exact["logits"], mirror["logits"])
+    m.close()
+
+
+def test_dense_overlap_does_not_change_results(binding):
+    """Bottom-FC on the side stream or in order: same kernels, same bits; and a
+    run of back-to-back forwards with different inputs keeps them apart."""
+    say("overlap on/off")
+    g = np.random.default_rng(31)
+    T, R, D, B, F = 6, 300, 32, 333, 40
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(np.float16) for _ in range(T)]
+    bottom, top = small_mlps(g, F, D, T, (128, 64), (256, 128))
+    m = H.make_model(binding, tabs, bottom, top, B, 60 * T * B, F)
+    batches = []
+    for _ in range(3):
+        lens = g.integers(0, 60, T * B).astype(np.int32)
+        idx = g.integers(0, R, int(lens.sum())).astype(np.int32)
+        batches.append(synth.Batch(g.standard_normal((B, F)).astype(np.float32), idx, lens))
+    dev = [(torch.from_numpy(b.dense).cuda(), torch.from_numpy(b.indices).cuda(),
+            torch.from_numpy(b.lengths).cuda()) for b in batches]
+    outs = {}
+    for overlap in (1, 0):
+        m.set_option(binding.REC_OPT_OVERLAP_DENSE, overlap)
+        res = [torch.empty(B, dtype=torch.float32, device="cuda") for _ in range(12)]
+        for i in range(12):                       # no synchronisation in between
+            d, ix, ln = dev[i % 3]
+            m.forward(d, ix, ln, res[i])
+        torch.cuda.synchronize()
+        outs[overlap] = [r.cpu().numpy() for r in res]
+        assert m.check() == (binding.REC_OK, -1)
+    for i in range(12):
+        assert np.array_equal(outs[1][i], outs[0][i])
+        assert np.array_equal(outs[1][i], outs[1][i % 3])
+    for i in range(3):
+        b = batches[i]
+        exact = orc.forward(b.dense, tabs, b.indices, b.lengths, bottom, top)
+        mirror = orc.forward(b.dense, tabs, b.indices, b.lengths, bottom, top, orc.BF16_MIRROR)
+        H.check_logits(outs[1][i], exact["logits"], mirror["logits"])
     m.close()
 
 
