@@ -21,6 +21,28 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 
+# HBM traffic of one pooling launch from rocprofv3 counter runs (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy: 2.000 and
+# 1.000), see profiles/pool_rmc2_counters.md.  Valid only for the kernel source
+# the counters were taken with; reported as null once csrc/pool.hip differs.
+POOL_TRAFFIC = {
+    "sha256": "c49be4a068716d219cedf3b3a32fc300e91a6a0b40a9179c618037605bf46205",
+    ("rmc2", 4096): {"fetch_bytes": 553996796.0, "write_bytes": 41943050.0},
+    ("rmc2-uniform", 4096): {"fetch_bytes": 1707535117.0, "write_bytes": 41943198.0},
+}
+
+
+def measured_pool_traffic(w):
+    import hashlib
+    src = os.path.join(ROOT, "paper_2203_07424_amd", "csrc", "pool.hip")
+    rec = POOL_TRAFFIC.get((w.name, w.batch))
+    if rec is None or not os.path.exists(src):
+        return None
+    with open(src, "rb") as f:
+        if hashlib.sha256(f.read()).hexdigest() != POOL_TRAFFIC["sha256"]:
+            return None
+    return rec["fetch_bytes"] + rec["write_bytes"]
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -166,7 +188,7 @@ def main() -> int:
         achieved = pool_bytes / (stage_avg["pool"] * 1e-3) / 1e9
         roofline = {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm",
                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                    "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_pool_traffic(w),
                     "bytes_per_launch": float(pool_bytes), "avg_launch_ms": stage_avg["pool"],
                     "launches_timed": n_timed}
 
