@@ -5,7 +5,13 @@ One step = one rec_forward() over one synthetic batch: offsets scan, embedding
 bag pooling, Bottom-FC, pairwise-dot interaction, Predict-FC.  Inputs and
 tables are resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--steps K] [--warmup W] [--workload rmc2] [--uniform]
+The timed region runs one model instance on one stream.  --instances N
+co-locates N instances (own stream and workspace each, tables shared) which
+take the K steps in turn; the default run also reports such a leg, measured
+after the timed region, under "co_located".
+
+  python bench.py [--steps K] [--warmup W] [--workload rmc2] [--uniform] [--instances N]
+  python bench.py --workload rmc2-large --latency-sweep
 """
 from __future__ import annotations
 
@@ -75,6 +81,128 @@ def cpu_baseline(w, batch, bottom, top, n_samples: int) -> dict:
                       f"materialised in compact tables), whole forward, {dt:.2f} s wall"}
 
 
+def build_model(binding, synth, torch, w, max_batch, share_tables=None):
+    """Model of workload `w` with tables filled on the device (or shared with
+    the model `share_tables`) and packed MLPs."""
+    dev = torch.device("cuda:0")
+    hi = w.pooling[1] if w.pooling[0] == "fixed" else w.pooling[3]
+    m = binding.RecModel(w.num_tables, w.emb_dim, [w.rows] * w.num_tables, w.table_dtype,
+                         w.num_dense, list(w.bottom), list(w.top), max_batch,
+                         min(max_batch * w.num_tables * hi, 2 ** 31 - 1))
+    tdt = torch.float16 if w.table_dtype == "f16" else torch.float32
+    for t in range(w.num_tables):
+        if share_tables is not None:
+            tab = share_tables.tables[t]
+        else:
+            tab = torch.empty((w.rows, w.emb_dim), dtype=tdt, device=dev)
+            assert binding.rec_synth_fill_table(tab, w.seed, t) == binding.REC_OK
+        m.load_table(t, tab)
+    bottom, top = synth.draw_mlp(w, "bottom"), synth.draw_mlp(w, "top")
+    for i, (W, b) in enumerate(bottom):
+        m.load_mlp(binding.REC_BOTTOM, i, torch.from_numpy(W), torch.from_numpy(b))
+    for i, (W, b) in enumerate(top):
+        m.load_mlp(binding.REC_TOP, i, torch.from_numpy(W), torch.from_numpy(b))
+    torch.cuda.synchronize()
+    return m, bottom, top
+
+
+def pick_concurrent_streams(torch, dev, n):
+    """n streams that really run side by side.
+
+    HIP deals its few hardware queues to streams in creation order, so two
+    streams may share one and then serialise.  Each candidate is probed with a
+    pair of spin kernels: on separate queues the pair takes about as long as
+    one of them."""
+    cand = [torch.cuda.Stream(device=dev) for _ in range(8)]
+    if n <= 1:
+        return cand[:1]
+    spin = 2_000_000
+
+    def pair_ms(a, b):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for s in (a, b):
+            with torch.cuda.stream(s):
+                torch.cuda._sleep(spin)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3
+
+    pair_ms(cand[0], cand[1])                      # warm-up
+    alone = min(pair_ms(cand[0], cand[0]) for _ in range(2)) / 2
+    chosen = [cand[0]]
+    for c in cand[1:]:
+        if len(chosen) == n:
+            break
+        if all(min(pair_ms(c, o) for _ in range(2)) < 1.5 * alone for o in chosen):
+            chosen.append(c)
+    if len(chosen) < n:
+        log(f"only {len(chosen)} concurrent streams found for {n} instances")
+        chosen += [cand[i] for i in range(8) if cand[i] not in chosen][:n - len(chosen)]
+    return chosen
+
+
+def latency_sweep(args) -> int:
+    """Per-batch latency over a batch-size sweep and the latency-bounded
+    throughput (Sec. II-B: throughput under an SLA tail-latency target).
+    Closed loop, one batch in flight, so queuing delay is not included."""
+    import numpy as np
+    import torch
+    from paper_2203_07424_amd import binding, synth
+
+    w0 = synth.WORKLOADS[args.workload]
+    sizes = [int(x) for x in args.sweep_batches.split(",")]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t0 = time.time()
+    m, _, _ = build_model(binding, synth, torch, w0, max(sizes))
+    log(f"model {w0.name} resident ({time.time() - t0:.1f} s)")
+    cdf = synth.zipf_cdf(w0.rows, float(w0.index_dist[1])) if w0.index_dist[0] == "zipf" else None
+    rows = []
+    for B in sizes:
+        w = w0.with_batch(B)
+        hb = [synth.draw_batch(w, 1000 + i, cdf) for i in range(2)]
+        db = [(torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
+               torch.from_numpy(b.lengths).to(dev)) for b in hb]
+        logits = torch.empty(B, dtype=torch.float32, device=dev)
+        for i in range(args.warmup):
+            m.forward(*db[i % 2], logits)
+        torch.cuda.synchronize()
+        lat = np.empty(args.sweep_iters)
+        for i in range(args.sweep_iters):
+            t = time.perf_counter()
+            m.forward(*db[i % 2], logits)
+            torch.cuda.synchronize()
+            lat[i] = time.perf_counter() - t
+        st, pos = m.check()
+        assert st == binding.REC_OK, (st, pos)
+        rows.append({"batch": B, "mean_nnz": float(np.mean([b.nnz for b in hb])),
+                     "p50_ms": float(np.percentile(lat, 50) * 1e3),
+                     "p99_ms": float(np.percentile(lat, 99) * 1e3),
+                     "max_ms": float(lat.max() * 1e3),
+                     "samples_per_s": float(B / lat.mean())})
+        log(f"B={B}: p50 {rows[-1]['p50_ms']:.3f} ms p99 {rows[-1]['p99_ms']:.3f} ms "
+            f"{rows[-1]['samples_per_s'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
+        del db, logits
+    ok = [r for r in rows if r["p99_ms"] <= args.sla_ms]
+    best = max(ok, key=lambda r: r["samples_per_s"]) if ok else None
+    out = {"metric": f"latency-bounded samples/s per GPU at p99 <= {args.sla_ms} ms per batch",
+           "value": best["samples_per_s"] if best else None, "unit": "samples/s", "n_gpus": 1,
+           "steps": args.sweep_iters, "warmup": args.warmup,
+           "ms_per_step": best["p50_ms"] if best else None, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None,
+           "dtype": "f16 tables -> f32 accumulate; bf16 MFMA -> f32 accumulate",
+           "data": "synthetic",
+           "config": {"workload": f"{w0.name}: {w0.num_tables} tables x {w0.rows} rows x dim "
+                                  f"{w0.emb_dim} {w0.table_dtype}, ids {w0.index_dist}",
+                      "best_batch": best["batch"] if best else None, "sla_ms": args.sla_ms,
+                      "note": "closed loop, one batch in flight; per-batch latency includes the "
+                              "host's launch calls; queuing delay excluded"},
+           "sweep": rows}
+    print(json.dumps(out), flush=True)
+    m.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,7 +212,15 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--uniform", action="store_true", help="uniform ids instead of Zipf")
     ap.add_argument("--batches", type=int, default=4, help="distinct input batches cycled")
-    ap.add_argument("--cpu-samples", type=int, default=1024)
+    ap.add_argument("--instances", type=int, default=1,
+                    help="co-located model instances in the timed region, each on its own "
+                         "stream, sharing the tables")
+    ap.add_argument("--colocated-leg", type=int, default=2,
+                    help="instances of the extra co-located leg run after the timed region "
+                         "(0 or 1 = none)")
+    ap.add_argument("--extra-steps", type=int, default=30,
+                    help="steps of each extra single-instance leg (0 = none)")
+    ap.add_argument("--cpu-samples", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known "
@@ -95,10 +231,18 @@ def main() -> int:
                     help="bracket the stages of every N-th timed step with HIP events")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="do not bracket stages with events inside the timed region")
+    ap.add_argument("--latency-sweep", action="store_true",
+                    help="batch-size sweep with per-batch latency percentiles instead of the "
+                         "throughput run (meant for --workload rmc2-large)")
+    ap.add_argument("--sweep-batches", default="64,256,1024,4096,16384")
+    ap.add_argument("--sweep-iters", type=int, default=200)
+    ap.add_argument("--sla-ms", type=float, default=20.0)
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
         return 2
+    if args.latency_sweep:
+        return latency_sweep(args)
 
     import numpy as np
     import torch
@@ -111,40 +255,40 @@ def main() -> int:
         w = w.with_uniform_indices()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    n_inst = max(1, args.instances)
 
     t0 = time.time()
-    hi = w.pooling[1] if w.pooling[0] == "fixed" else w.pooling[3]
-    m = binding.RecModel(w.num_tables, w.emb_dim, [w.rows] * w.num_tables, w.table_dtype,
-                         w.num_dense, list(w.bottom), list(w.top), w.batch,
-                         w.batch * w.num_tables * hi)
-    tdt = torch.float16 if w.table_dtype == "f16" else torch.float32
-    for t in range(w.num_tables):
-        tab = torch.empty((w.rows, w.emb_dim), dtype=tdt, device=dev)
-        assert binding.rec_synth_fill_table(tab, w.seed, t) == binding.REC_OK
-        m.load_table(t, tab)
-    bottom, top = synth.draw_mlp(w, "bottom"), synth.draw_mlp(w, "top")
-    for i, (W, b) in enumerate(bottom):
-        m.load_mlp(binding.REC_BOTTOM, i, torch.from_numpy(W), torch.from_numpy(b))
-    for i, (W, b) in enumerate(top):
-        m.load_mlp(binding.REC_TOP, i, torch.from_numpy(W), torch.from_numpy(b))
+    m, bottom, top = build_model(binding, synth, torch, w, w.batch)
+    # Co-located instances (Sec. II-B, model co-location on the accelerator): each
+    # has its own workspace and stream; tables are shared, not copied.
+    models = [m] + [build_model(binding, synth, torch, w, w.batch, share_tables=m)[0]
+                    for _ in range(n_inst - 1)]
     if args.overlap:
-        m.set_option(binding.REC_OPT_OVERLAP_DENSE, 1)
+        for mm in models:
+            mm.set_option(binding.REC_OPT_OVERLAP_DENSE, 1)
+    streams = pick_concurrent_streams(torch, dev, n_inst)
     torch.cuda.synchronize()
-    log(f"model {w.name}: {w.num_tables} x {w.rows} x {w.emb_dim} {w.table_dtype} resident "
-        f"({time.time() - t0:.1f} s)")
+    log(f"model {w.name}: {w.num_tables} x {w.rows} x {w.emb_dim} {w.table_dtype} resident, "
+        f"{n_inst} instance(s) ({time.time() - t0:.1f} s)")
 
-    cdf = synth.zipf_cdf(w.rows, float(w.index_dist[1])) if w.index_dist[0] == "zipf" else None
-    host_batches = [synth.draw_batch(w, i, cdf) for i in range(args.batches)]
-    dev_batches = [(torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
-                    torch.from_numpy(b.lengths).to(dev)) for b in host_batches]
-    logits = torch.empty(w.batch, dtype=torch.float32, device=dev)
+    def make_batches(wl, n, first_id):
+        cdf = synth.zipf_cdf(wl.rows, float(wl.index_dist[1])) if wl.index_dist[0] == "zipf" else None
+        hb = [synth.draw_batch(wl, first_id + i, cdf) for i in range(n)]
+        db = [(torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
+               torch.from_numpy(b.lengths).to(dev)) for b in hb]
+        return hb, db
+
+    host_batches, dev_batches = make_batches(w, args.batches, 0)
+    logits = [torch.empty(w.batch, dtype=torch.float32, device=dev) for _ in range(n_inst)]
     torch.cuda.synchronize()
     log(f"{args.batches} batches of {w.batch} resident, nnz[0] = {host_batches[0].nnz} "
         f"({time.time() - t0:.1f} s)")
 
     def step(i):
+        k = i % n_inst
         d, idx, lens = dev_batches[i % len(dev_batches)]
-        m.forward(d, idx, lens, logits)
+        with torch.cuda.stream(streams[k]):
+            models[k].forward(d, idx, lens, logits[k])
 
     if args.calibration_copy_mib:
         n = args.calibration_copy_mib << 20
@@ -158,11 +302,14 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    st, pos = m.check()
-    assert st == binding.REC_OK, (st, pos)
+    for mm in models:
+        st, pos = mm.check()
+        assert st == binding.REC_OK, (st, pos)
 
+    # Stage events are recorded by instance 0 on every event_period-th of ITS steps.
     use_events = not args.no_stage_events
-    n_timed = (args.steps + args.event_period - 1) // args.event_period
+    steps0 = (args.steps + n_inst - 1) // n_inst            # forwards instance 0 will run
+    n_timed = (steps0 + args.event_period - 1) // args.event_period
     if use_events:
         m.set_profiling(n_timed, args.event_period)
     torch.cuda.synchronize()
@@ -175,22 +322,77 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / args.steps
     value = w.batch * args.steps / elapsed
 
-    stage_avg = None
-    roofline = None
-    if use_events:
+    def collect(model, count, batches_used, wl):
         acc = np.zeros(binding.REC_NUM_STAGES)
-        for j in range(n_timed):
-            acc += np.array(list(m.stage_ms(j).values()))
-        stage_avg = dict(zip(binding.STAGE_NAMES, (acc / n_timed).tolist()))
-        m.set_profiling(0)
-        pool_bytes = np.mean([algorithmic_pool_bytes(w, host_batches[i % len(host_batches)])
-                              for i in range(0, args.steps, args.event_period)])
-        achieved = pool_bytes / (stage_avg["pool"] * 1e-3) / 1e9
-        roofline = {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm",
-                    "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_pool_traffic(w),
-                    "bytes_per_launch": float(pool_bytes), "avg_launch_ms": stage_avg["pool"],
-                    "launches_timed": n_timed}
+        for j in range(count):
+            acc += np.array(list(model.stage_ms(j).values()))
+        avg = dict(zip(binding.STAGE_NAMES, (acc / count).tolist()))
+        model.set_profiling(0)
+        pool_bytes = float(np.mean([algorithmic_pool_bytes(wl, b) for b in batches_used]))
+        achieved = pool_bytes / (avg["pool"] * 1e-3) / 1e9
+        return avg, {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_pool_traffic(wl),
+                     "bytes_per_launch": pool_bytes, "avg_launch_ms": avg["pool"],
+                     "launches_timed": count}
+
+    stage_avg = roofline = None
+    if use_events:
+        used = [host_batches[(j * args.event_period * n_inst) % len(host_batches)] for j in range(n_timed)]
+        stage_avg, roofline = collect(m, n_timed, used, w)
+        roofline["instances_sharing_the_gpu"] = n_inst
+
+    # Two short extra legs, one instance alone on the GPU, every step bracketed:
+    # the same workload, and its uniform-id twin (no cache reuse: the run on
+    # which pooling is compared with the HBM peak).
+    extra = {}
+    if use_events and args.extra_steps > 0:
+        def solo(db, hb, wl):
+            for i in range(5):
+                m.forward(*db[i % len(db)], logits[0])
+            torch.cuda.synchronize()
+            m.set_profiling(args.extra_steps, 1)
+            for i in range(args.extra_steps):
+                m.forward(*db[i % len(db)], logits[0])
+            torch.cuda.synchronize()
+            return collect(m, args.extra_steps, [hb[i % len(hb)] for i in range(args.extra_steps)], wl)
+        if n_inst > 1:
+            st_solo, rf_solo = solo(dev_batches, host_batches, w)
+            extra["roofline_single_instance"] = rf_solo
+            extra["stage_ms_single_instance"] = st_solo
+        if w.index_dist[0] == "zipf":
+            wu = w.with_uniform_indices()
+            hbu, dbu = make_batches(wu, 2, 500)
+            st_u, rf_u = solo(dbu, hbu, wu)
+            extra["roofline_uniform_ids"] = rf_u
+            del dbu
+
+    # Model co-location on the accelerator (Sec. II-B): the same K steps dealt to
+    # several instances on streams of their own; small kernels of one instance
+    # fill the gaps of the other's pooling.
+    if n_inst == 1 and args.colocated_leg > 1:
+        nc = args.colocated_leg
+        cm = [m] + [build_model(binding, synth, torch, w, w.batch, share_tables=m)[0]
+                    for _ in range(nc - 1)]
+        cs = pick_concurrent_streams(torch, dev, nc)
+        cl = [torch.empty(w.batch, dtype=torch.float32, device=dev) for _ in range(nc)]
+
+        def cstep(i):
+            with torch.cuda.stream(cs[i % nc]):
+                cm[i % nc].forward(*dev_batches[i % len(dev_batches)], cl[i % nc])
+        for i in range(args.warmup):
+            cstep(i)
+        torch.cuda.synchronize()
+        tc = time.perf_counter()
+        for i in range(args.steps):
+            cstep(i)
+        torch.cuda.synchronize()
+        ec = time.perf_counter() - tc
+        extra["co_located"] = {"instances": nc, "value": w.batch * args.steps / ec,
+                               "unit": "samples/s", "ms_per_step": ec * 1e3 / args.steps,
+                               "steps": args.steps}
+        for mm in cm[1:]:
+            mm.close()
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -207,11 +409,14 @@ def main() -> int:
                                f"{w.table_dtype}, pooling {w.pooling}, ids {w.index_dist}, "
                                f"bottom {list(w.bottom)}, top {list(w.top)}",
                    "batch": w.batch, "distinct_batches": args.batches,
+                   "co_located_instances": n_inst,
                    "mean_nnz": float(np.mean([b.nnz for b in host_batches]))},
         "roofline": roofline, "cpu_baseline": cpu, "stage_ms": stage_avg,
     }
+    out.update(extra)
     print(json.dumps(out), flush=True)
-    m.close()
+    for mm in models:
+        mm.close()
     return 0
 
 

@@ -316,3 +316,27 @@ def test_full_size_workload_sampled_against_oracle(binding, name, n_check):
     assert np.isfinite(logits).all()
     m.close()
     torch.cuda.empty_cache()
+
+
+def test_large_capacity_variant_sampled_against_oracle(binding):
+    """154 GB of tables: rows sit beyond 2 GiB inside a table, so this is the
+    case that needs 64-bit row addressing.  Skipped where the device is smaller."""
+    w = synth.WORKLOADS["rmc2-large"].with_batch(512)
+    free, _ = torch.cuda.mem_get_info()
+    need = w.num_tables * w.rows * w.emb_dim * 2 + (8 << 30)
+    if free < need:
+        pytest.skip(f"needs {need >> 30} GiB of device memory, {free >> 30} GiB free")
+    say("large-capacity workload, batch", w.batch)
+    m, bottom, top = H.make_workload_model(binding, w)
+    batch = synth.draw_batch(w, 0)
+    assert batch.indices.max() > (1 << 24)          # byte offsets beyond 2^31 are exercised
+    logits = H.run(m, batch)
+    assert m.check() == (binding.REC_OK, -1)
+    pick = np.array([0, 1, 255, 256, 510, 511])
+    exact = H.oracle_on_slice(w, batch, pick, bottom, top)
+    mirror = H.oracle_on_slice(w, batch, pick, bottom, top, orc.BF16_MIRROR)
+    pooled = m.debug_pooled()[torch.from_numpy(pick).cuda()].cpu().numpy()
+    H.check_pooled(pooled, exact["pooled"], exact["abs_sum"])
+    H.check_logits(logits[pick], exact["logits"], mirror["logits"])
+    m.close()
+    torch.cuda.empty_cache()
