@@ -26,10 +26,17 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 #ifndef REC_IT_THREADS
-#define REC_IT_THREADS 128
+#define REC_IT_THREADS 256
 #endif
 constexpr int IT_THREADS = REC_IT_THREADS;
 constexpr int IT_WAVES = IT_THREADS / 64;
+#ifndef REC_IT_BATCH
+#define REC_IT_BATCH 4
+#endif
+constexpr int IT_BATCH = REC_IT_BATCH;  // 16-byte loads in flight per thread while staging
+#ifndef REC_IT_TILES_PER_WAVE
+#define REC_IT_TILES_PER_WAVE 1
+#endif
 
 struct Geometry {
     int V, Vpad, nblk, ntile, d4, ksteps, swmask;
@@ -69,17 +76,17 @@ __global__ __launch_bounds__(IT_THREADS) void interact_kernel(const float *__res
 
     // Stage X: row 0 = x0, rows 1..T = pooled (contiguous), rows V..Vpad = 0.
     // d4 is a power of two, so rows and columns come from shifts; loads are
-    // issued four at a time before their LDS stores.
+    // issued IT_BATCH at a time before their LDS stores.
     const int ld4 = __ffs(g.d4) - 1, n4 = g.Vpad << ld4;  // 16-byte words of X per sample
     for (int s = 0; s < ns; ++s) {
         const long long b = b0 + s;
         const float *px0 = x0 + b * ldx0;
         const float *pp = pooled + b * T * D - D;  // row r >= 1 sits at pp + r * D
         float *dst = sX + s * g.x_floats;
-        for (int f0 = tid; f0 < n4; f0 += 4 * IT_THREADS) {
-            f32x4 v[4];
+        for (int f0 = tid; f0 < n4; f0 += IT_BATCH * IT_THREADS) {
+            f32x4 v[IT_BATCH];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < IT_BATCH; ++u) {
                 const int f = f0 + u * IT_THREADS;
                 const int row = f >> ld4, c4 = f & (g.d4 - 1);
                 v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -87,7 +94,7 @@ __global__ __launch_bounds__(IT_THREADS) void interact_kernel(const float *__res
                     v[u] = *reinterpret_cast<const f32x4 *>((row == 0 ? px0 : pp + (size_t)row * D) + 4 * c4);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < IT_BATCH; ++u) {
                 const int f = f0 + u * IT_THREADS;
                 const int row = f >> ld4, c4 = f & (g.d4 - 1);
                 if (f < n4)
@@ -177,10 +184,10 @@ hipError_t launch_interact(const float *x0, int ldx0, const float *pooled, int B
     const Geometry g = geometry(T, D);
     const size_t per = g.x_floats * sizeof(float) + (size_t)ldo * 2;
     if (per > 64 * 1024) return hipErrorInvalidValue;  // rejected at model creation
-    // Enough samples per block to give every wave about two tiles; small blocks
+    // Enough samples per block to give every wave about one tile; small blocks
     // (little LDS each) keep many of them resident, which hides the staging
     // latency of one behind the matrix work of the others.
-    int spb = (2 * IT_WAVES + g.ntile - 1) / g.ntile;
+    int spb = (REC_IT_TILES_PER_WAVE * IT_WAVES + g.ntile - 1) / g.ntile;
     while (spb > 1 && spb * per > 32 * 1024) --spb;
     const dim3 grid((B + spb - 1) / spb), block(IT_THREADS);
     __bf16 *o = static_cast<__bf16 *>(out_bf16);
