@@ -225,6 +225,9 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known "
                          "traffic to scale hardware counters by)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the distinct batches' forwards into one HIP graph and replay "
+                         "it (steps are rounded to whole replays; no stage events)")
     ap.add_argument("--overlap", action="store_true",
                     help="run Bottom-FC on the library's side stream beside scan and pooling")
     ap.add_argument("--event-period", type=int, default=10,
@@ -289,6 +292,23 @@ def main() -> int:
         d, idx, lens = dev_batches[i % len(dev_batches)]
         with torch.cuda.stream(streams[k]):
             models[k].forward(d, idx, lens, logits[k])
+
+    if args.graph:
+        # One replay = one forward over each distinct batch, single instance.
+        assert n_inst == 1
+        per = len(dev_batches)
+        glog = [torch.empty(w.batch, dtype=torch.float32, device=dev) for _ in range(per)]
+        with torch.cuda.stream(streams[0]):
+            cap = binding.CapturedForward(m, dev_batches, glog)
+        args.steps = max(per, args.steps // per * per)
+        args.no_stage_events = True
+        args.colocated_leg = 0
+        args.extra_steps = 0
+
+        def step(i):                                    # noqa: F811
+            if i % per == 0:
+                with torch.cuda.stream(streams[0]):
+                    cap.replay()
 
     if args.calibration_copy_mib:
         n = args.calibration_copy_mib << 20
@@ -409,7 +429,7 @@ def main() -> int:
                                f"{w.table_dtype}, pooling {w.pooling}, ids {w.index_dist}, "
                                f"bottom {list(w.bottom)}, top {list(w.top)}",
                    "batch": w.batch, "distinct_batches": args.batches,
-                   "co_located_instances": n_inst,
+                   "co_located_instances": n_inst, "hip_graph": bool(args.graph),
                    "mean_nnz": float(np.mean([b.nnz for b in host_batches]))},
         "roofline": roofline, "cpu_baseline": cpu, "stage_ms": stage_avg,
     }

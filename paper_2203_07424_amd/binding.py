@@ -285,3 +285,26 @@ class RecModel:
         st, p, ld = rec_debug_get(self.handle, REC_DBG_INTERACT)
         raw, ld = self._view(REC_DBG_INTERACT, 2 * B * ld)
         return raw.view(torch.bfloat16).view(B, ld).clone()
+
+
+class CapturedForward:
+    """One or more forwards recorded into a HIP graph and replayed with a single launch.
+
+    rec_forward() only enqueues kernels (no allocation, no synchronisation, no
+    memset), so it can be recorded under stream capture.  The graph replays the
+    recorded pointers: callers keep `batches` and `logits` alive and refresh
+    their contents in place.  Stage events must be off while recording."""
+
+    def __init__(self, model: RecModel, batches, logits):
+        self.model, self.batches, self.logits = model, list(batches), list(logits)
+        assert len(self.batches) == len(self.logits) and self.batches
+        for (d, i, l), out in zip(self.batches, self.logits):   # warm-up outside capture
+            model.forward(d, i, l, out)
+        torch.cuda.synchronize(model.device)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            for (d, i, l), out in zip(self.batches, self.logits):
+                model.forward(d, i, l, out)
+
+    def replay(self) -> None:
+        self.graph.replay()

@@ -341,6 +341,12 @@ hipError_t launch_fc(const void *A, bool a_f32, int lda, int M, int K, int Kpad,
         if (Npad == 64) return launch_tile<64, 64, 2, 4>(a, s);
         return hipErrorInvalidValue;
     }
+#ifdef REC_FC_FORCE
+    if (REC_FC_FORCE == 1 && Npad % 128 == 0) return launch_tile<128, 128, 2, 2>(a, s);
+    if (REC_FC_FORCE == 2) return launch_tile<64, 64, 2, 4>(a, s);
+    if (REC_FC_FORCE == 3 && Npad % 128 == 0) return launch_tile<32, 128, 1, 4>(a, s);
+    if (REC_FC_FORCE == 4 && Npad % 128 == 0) return launch_tile<64, 128, 1, 4>(a, s);
+#endif
     // Large tiles only where they still give every compute unit a block.
     const long long big_blocks = (long long)(Npad / 128) * ((M + 127) / 128);
     if (Npad % 128 == 0 && big_blocks >= 256) return launch_tile<128, 128, 2, 2>(a, s);

@@ -250,6 +250,46 @@ def test_dense_overlap_does_not_change_results(binding):
     m.close()
 
 
+def test_graph_replays_match_eager_forwards(binding):
+    """A recorded forward is replayed several times with eager work and
+    synchronisations in between; every replay must give the eager bits, also
+    after the input buffers were refreshed in place."""
+    say("graph replay")
+    g = np.random.default_rng(41)
+    T, R, D, B, F = 5, 400, 32, 190, 24
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(np.float32) for _ in range(T)]
+    bottom, top = small_mlps(g, F, D, T, (64,), (128, 64))
+    L = 12                                              # fixed lengths: nnz stays the same
+    m = H.make_model(binding, tabs, bottom, top, B, L * T * B, F)
+
+    def draw():
+        lens = np.full(T * B, L, np.int32)
+        idx = g.integers(0, R, L * T * B).astype(np.int32)
+        return synth.Batch(g.standard_normal((B, F)).astype(np.float32), idx, lens)
+    first = draw()
+    bufs = (torch.from_numpy(first.dense).cuda(), torch.from_numpy(first.indices).cuda(),
+            torch.from_numpy(first.lengths).cuda())
+    out = torch.empty(B, dtype=torch.float32, device="cuda")
+    cap = binding.CapturedForward(m, [bufs], [out])
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for rep in range(5):
+        b = first if rep == 0 else draw()
+        bufs[0].copy_(torch.from_numpy(b.dense))
+        bufs[1].copy_(torch.from_numpy(b.indices))
+        out.zero_()
+        cap.replay()
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().copy()
+        scratch.add_(1.0)                               # unrelated eager work between replays
+        eager = H.run(m, b)
+        assert np.array_equal(got, eager), rep
+        assert m.check() == (binding.REC_OK, -1)
+    exact = orc.forward(b.dense, tabs, b.indices, b.lengths, bottom, top)
+    mirror = orc.forward(b.dense, tabs, b.indices, b.lengths, bottom, top, orc.BF16_MIRROR)
+    H.check_logits(got, exact["logits"], mirror["logits"])
+    m.close()
+
+
 def test_forward_hand_worked_example_is_exact_on_device(binding):
     import json, os
     say("hand example")
