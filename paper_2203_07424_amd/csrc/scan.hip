@@ -4,8 +4,10 @@
 // factor varies per lookup, Fig. 2(c)); the gather needs where each bag starts.
 // Two passes over at most a few hundred thousand int32: per-tile sums, then
 // per-tile scans in LDS that first reduce the sums of the tiles before them.
-// (One launch in which every block re-reads the earlier lengths itself was
-// measured 5x slower: a single block pulls only tens of GB/s.)
+// One-launch variants were measured and dropped: blocks re-reading the earlier
+// lengths themselves (5x slower, a single block pulls only tens of GB/s); tile
+// totals reduced by each pooling wave (+28 us of pooling for -3 us of scan);
+// a last-block-done ticket (its device-scope fences cost more than a launch).
 #include "rec_internal.h"
 
 namespace rec {

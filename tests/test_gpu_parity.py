@@ -64,7 +64,7 @@ POOL_CASES = [
     (1, 200, 256, np.float32, 9, 0, 17),       # 1 KB rows: one row per load
     (2, 100, 128, np.float16, 40, 0, 300),     # long bags
     (5, 2000, 16, np.float32, 1500, 0, 12),    # T*B spans several scan tiles
-    (3, 500, 4, np.float32, 100_000, 0, 3),    # 300,000 bags: the two-pass scan
+    (3, 500, 4, np.float32, 100_000, 0, 3),    # 300,000 bags: 147 scan tiles
 ]
 
 
