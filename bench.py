@@ -225,6 +225,9 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known "
                          "traffic to scale hardware counters by)")
+    ap.add_argument("--hot-rows", type=int, default=0,
+                    help="register the N most frequent rows of each table (profiled on two "
+                         "batches that are not timed) so that pooling serves them from LDS")
     ap.add_argument("--graph", action="store_true",
                     help="record the distinct batches' forwards into one HIP graph and replay "
                          "it (steps are rounded to whole replays; no stage events)")
@@ -269,6 +272,13 @@ def main() -> int:
     if args.overlap:
         for mm in models:
             mm.set_option(binding.REC_OPT_OVERLAP_DENSE, 1)
+    if args.hot_rows > 0:
+        pcdf = synth.zipf_cdf(w.rows, float(w.index_dist[1])) if w.index_dist[0] == "zipf" else None
+        hot = synth.profile_hot_rows(w, [900, 901], args.hot_rows, pcdf)
+        for mm in models:
+            for t in range(w.num_tables):
+                mm.load_hot_rows(t, hot[t])
+        log(f"hot rows: {args.hot_rows} per table from profiling batches 900, 901 ({time.time() - t0:.1f} s)")
     streams = pick_concurrent_streams(torch, dev, n_inst)
     torch.cuda.synchronize()
     log(f"model {w.name}: {w.num_tables} x {w.rows} x {w.emb_dim} {w.table_dtype} resident, "
@@ -429,7 +439,7 @@ def main() -> int:
                                f"{w.table_dtype}, pooling {w.pooling}, ids {w.index_dist}, "
                                f"bottom {list(w.bottom)}, top {list(w.top)}",
                    "batch": w.batch, "distinct_batches": args.batches,
-                   "co_located_instances": n_inst, "hip_graph": bool(args.graph),
+                   "co_located_instances": n_inst, "hip_graph": bool(args.graph), "hot_rows_per_table": args.hot_rows,
                    "mean_nnz": float(np.mean([b.nnz for b in host_batches]))},
         "roofline": roofline, "cpu_baseline": cpu, "stage_ms": stage_avg,
     }

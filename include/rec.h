@@ -122,6 +122,20 @@ REC_API rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes,
  * (REC_ERR_STATE otherwise); copies one descriptor to the device and waits. */
 REC_API rec_status rec_load_tables(rec_model *m, int32_t table, const void *dev_rows);
 
+/* Longest hot list rec_load_hot_rows() accepts. */
+#define REC_MAX_HOT_ROWS 1024
+
+/* Registers the hot rows of table `table` (locality-aware embedding partition,
+ * Sec. IV-A: the entries accessed most often, found by profiling the id
+ * stream): dev_ids is int32 [n] row ids in device memory, borrowed for the
+ * life of the model.  With a hot list on any table the pooling kernel keeps a
+ * copy of the listed rows in LDS, refreshed from the table on every forward,
+ * and serves lookups of those ids from there; the pooled sums are the same.
+ * Ids listed twice or outside the table are ignored.  n = 0 removes the list.
+ * REC_ERR_ARG if n > REC_MAX_HOT_ROWS or n rows do not fit the 64 KB LDS
+ * budget (about 384 rows of 128 bytes); REC_ERR_STATE without a workspace. */
+REC_API rec_status rec_load_hot_rows(rec_model *m, int32_t table, const int32_t *dev_ids, int32_t n);
+
 /* Bytes of the packed form of one layer (bf16 weights padded to the tile grid
  * followed by fp32 bias); 0 on a bad layer id. */
 REC_API size_t rec_mlp_packed_bytes(const rec_model *m, int32_t which, int32_t layer);

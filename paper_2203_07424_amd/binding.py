@@ -33,7 +33,7 @@ REC_NUM_STAGES = 5
 STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top")
 
 EXPORTS = ("rec_create", "rec_destroy", "rec_workspace_bytes", "rec_bind_workspace",
-           "rec_load_tables", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_check",
+           "rec_load_tables", "rec_load_hot_rows", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_check",
            "rec_debug_get", "rec_set_option", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
            "rec_synth_fill_table")
 
@@ -58,6 +58,8 @@ _lib.rec_bind_workspace.restype = C.c_int
 _lib.rec_bind_workspace.argtypes = [_vp, _vp, C.c_size_t, _vp]
 _lib.rec_load_tables.restype = C.c_int
 _lib.rec_load_tables.argtypes = [_vp, C.c_int32, _vp]
+_lib.rec_load_hot_rows.restype = C.c_int
+_lib.rec_load_hot_rows.argtypes = [_vp, C.c_int32, _vp, C.c_int32]
 _lib.rec_mlp_packed_bytes.restype = C.c_size_t
 _lib.rec_mlp_packed_bytes.argtypes = [_vp, C.c_int32, C.c_int32]
 _lib.rec_load_mlp.restype = C.c_int
@@ -132,6 +134,11 @@ def rec_load_tables(m: int, table: int, dev_rows: torch.Tensor) -> int:
     return _lib.rec_load_tables(m, table, dev_rows.data_ptr())
 
 
+def rec_load_hot_rows(m: int, table: int, dev_ids: Optional[torch.Tensor]) -> int:
+    n = 0 if dev_ids is None else dev_ids.numel()
+    return _lib.rec_load_hot_rows(m, table, _ptr(dev_ids), n)
+
+
 def rec_mlp_packed_bytes(m: int, which: int, layer: int) -> int:
     return int(_lib.rec_mlp_packed_bytes(m, which, layer))
 
@@ -200,6 +207,7 @@ class RecModel:
         self.ws = torch.empty(rec_workspace_bytes(self.handle), dtype=torch.uint8, device=self.device)
         self._ok(rec_bind_workspace(self.handle, self.ws), "rec_bind_workspace")
         self.tables: List[Optional[torch.Tensor]] = [None] * num_tables
+        self.hot: List[Optional[torch.Tensor]] = [None] * num_tables
         self.packed: dict = {}
         self.last_batch = 0
 
@@ -223,6 +231,14 @@ class RecModel:
         assert dev_rows.is_cuda and dev_rows.is_contiguous() and dev_rows.dtype == self.table_dtype
         self._ok(rec_load_tables(self.handle, t, dev_rows), "rec_load_tables")
         self.tables[t] = dev_rows
+
+    def load_hot_rows(self, t: int, ids) -> None:
+        """ids: int32 row ids (tensor or array), or None / empty to remove the list."""
+        dev_ids = None
+        if ids is not None and len(ids) > 0:
+            dev_ids = torch.as_tensor(ids, dtype=torch.int32).to(self.device).contiguous()
+        self._ok(rec_load_hot_rows(self.handle, t, dev_ids), "rec_load_hot_rows")
+        self.hot[t] = dev_ids
 
     def load_mlp(self, which: int, layer: int, W: torch.Tensor, b: torch.Tensor) -> None:
         W = W.to(self.device, torch.float32).contiguous()

@@ -33,6 +33,8 @@ struct rec_model {
     std::vector<long long> rows;
     std::vector<Layer> bottom, top;
     std::vector<char> table_loaded;
+    std::vector<TableDesc> desc;  // host copy of the device descriptors
+    int num_cus = 256;
 
     // workspace carve-up (byte offsets)
     size_t off_err = 0, off_tables = 0, off_offsets = 0, off_tile_sums = 0, off_pooled = 0,
@@ -138,6 +140,8 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     m->max_batch = cfg->max_batch; m->max_nnz = cfg->max_nnz;
     m->rows.assign(cfg->rows, cfg->rows + T);
     m->table_loaded.assign(T, 0);
+    m->desc.assign(T, TableDesc{nullptr, 0, nullptr, 0, 0});
+    for (int t = 0; t < T; ++t) m->desc[t].rows = cfg->rows[t];
     m->d_pad = pad_up(D);
     m->z_ld = pad_up((int)width);
     m->act_ld = PAD;
@@ -198,8 +202,14 @@ rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *s
             hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess)
             return REC_ERR_DEVICE;
     }
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+        m->num_cus = cus;
     m->ws = static_cast<char *>(dev_ptr);
-    std::fill(m->table_loaded.begin(), m->table_loaded.end(), 0);  // descriptors live in the workspace
+    // The descriptors live in the workspace: tables and hot lists are to be registered again.
+    std::fill(m->table_loaded.begin(), m->table_loaded.end(), 0);
+    for (TableDesc &d : m->desc) { d.base = nullptr; d.hot_ids = nullptr; d.n_hot = 0; }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (launch_clear_err(m->at<ErrRecord>(m->off_err), s) != hipSuccess) return REC_ERR_DEVICE;
     if (hipStreamSynchronize(s) != hipSuccess) return REC_ERR_DEVICE;
@@ -211,11 +221,28 @@ rec_status rec_load_tables(rec_model *m, int32_t table, const void *dev_rows)
     if (!m || !dev_rows || table < 0 || table >= m->T) return REC_ERR_ARG;
     if (reinterpret_cast<uintptr_t>(dev_rows) % 16 != 0) return REC_ERR_ARG;
     if (!m->ws) return REC_ERR_STATE;
-    TableDesc d{dev_rows, m->rows[table]};
-    if (hipMemcpy(m->at<TableDesc>(m->off_tables) + table, &d, sizeof(d), hipMemcpyHostToDevice) !=
-        hipSuccess)
+    m->desc[table].base = dev_rows;
+    if (hipMemcpy(m->at<TableDesc>(m->off_tables) + table, &m->desc[table], sizeof(TableDesc),
+                  hipMemcpyHostToDevice) != hipSuccess)
         return REC_ERR_DEVICE;
     m->table_loaded[table] = 1;
+    return REC_OK;
+}
+
+rec_status rec_load_hot_rows(rec_model *m, int32_t table, const int32_t *dev_ids, int32_t n)
+{
+    if (!m || table < 0 || table >= m->T || n < 0 || n > REC_MAX_HOT_ROWS || (n > 0 && !dev_ids))
+        return REC_ERR_ARG;
+    if (!m->ws) return REC_ERR_STATE;
+    int hcap = 16;
+    while (hcap < n) hcap *= 2;
+    const int rowbytes = m->D * (m->dtype == REC_F16 ? 2 : 4);
+    if (n > 0 && !pool_hot_fits(hcap, rowbytes)) return REC_ERR_ARG;
+    m->desc[table].hot_ids = n > 0 ? dev_ids : nullptr;
+    m->desc[table].n_hot = n;
+    if (hipMemcpy(m->at<TableDesc>(m->off_tables) + table, &m->desc[table], sizeof(TableDesc),
+                  hipMemcpyHostToDevice) != hipSuccess)
+        return REC_ERR_DEVICE;
     return REC_OK;
 }
 
@@ -311,9 +338,24 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
     // S0
     REC_TRY(launch_scan(dev_lengths, T * B, nnz, offsets, m->at<long long>(m->off_tile_sums), err, s));
     REC_MARK();
-    // S1
-    REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
-                        pooled, err, s));
+    // S1: with hot lists registered, hot rows are served from LDS.
+    {
+        int hmax = 0;
+        for (const TableDesc &d : m->desc) hmax = d.n_hot > hmax ? d.n_hot : hmax;
+        if (hmax > 0) {
+            // Capacity: at least the longest list; a sparse hash (128 slots of rows
+            // or more, where LDS allows) keeps the per-wave probe chains short.
+            const int rowbytes = D * (m->dtype == REC_F16 ? 2 : 4);
+            int hcap = 16;
+            while (hcap < hmax) hcap *= 2;
+            while (hcap < 128 && pool_hot_fits(hcap * 2, rowbytes)) hcap *= 2;
+            REC_TRY(launch_pool_hot(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
+                                    pooled, hcap, m->num_cus, err, s));
+        } else {
+            REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
+                                pooled, err, s));
+        }
+    }
     REC_MARK();
     // S2, or the wait for it (the "bottom" stage then times only what pooling did not hide)
     if (overlap)

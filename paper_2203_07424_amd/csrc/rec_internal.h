@@ -21,6 +21,9 @@ enum : unsigned int { ERR_NEG_LENGTH = 1u, ERR_TOTAL_MISMATCH = 2u, ERR_INDEX_RA
 struct TableDesc {
     const void *base;
     long long rows;
+    const int32_t *hot_ids;  // rows worth caching in LDS (may be null)
+    int n_hot;
+    int pad;
 };
 
 // S0: one scan block covers SCAN_TILE lengths.
@@ -44,6 +47,13 @@ hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *of
 hipError_t launch_pool(const TableDesc *tables, int dtype, int T, int D, int B,
                        const int32_t *indices, const int32_t *offsets, float *pooled,
                        ErrRecord *err, hipStream_t s);
+
+// S1 with the tables' hot rows served from an LDS copy (hcap: power of two >= the
+// longest hot list, pool_hot_fits(hcap, rowbytes) must hold).
+bool pool_hot_fits(int hcap, int rowbytes);
+hipError_t launch_pool_hot(const TableDesc *tables, int dtype, int T, int D, int B,
+                           const int32_t *indices, const int32_t *offsets, float *pooled, int hcap,
+                           int num_cus, ErrRecord *err, hipStream_t s);
 
 // S2 / S4. C[m][n] = act(sum_k A[m][k] * W[n][k] + bias[n]) on bf16 MFMA.
 //   A: bf16 [M][lda] or (a_f32) fp32 [M][lda] with only k < K valid

@@ -234,6 +234,29 @@ def draw_mlp(w: Workload, which: str) -> List[Tuple[np.ndarray, np.ndarray]]:
     return layers
 
 
+def profile_hot_rows(w: Workload, batch_ids, n_hot: int, cdf: Optional[np.ndarray] = None):
+    """Per table, the n_hot row ids seen most often in the given (profiling)
+    batches, most frequent first: a stand-in for ranking rows by access
+    frequency over a production trace (Sec. IV-A).  Returns a list of int32 arrays."""
+    counts = [np.zeros(w.rows, dtype=np.int32) for _ in range(w.num_tables)]
+    for bid in batch_ids:
+        lengths = draw_lengths(w, bid)
+        ids = draw_indices(w, bid, lengths, cdf)
+        per_table = lengths.reshape(w.num_tables, w.batch).sum(axis=1, dtype=np.int64)
+        pos = 0
+        for t in range(w.num_tables):
+            n = int(per_table[t])
+            counts[t] += np.bincount(ids[pos:pos + n], minlength=w.rows).astype(np.int32)
+            pos += n
+    out = []
+    for t in range(w.num_tables):
+        k = min(n_hot, w.rows)
+        top = np.argpartition(counts[t], w.rows - k)[w.rows - k:]
+        top = top[np.argsort(-counts[t][top], kind="stable")]
+        out.append(top.astype(np.int32))
+    return out
+
+
 @dataclass
 class Batch:
     dense: np.ndarray      # float32 [B, F]

@@ -213,6 +213,76 @@ def test_forward_every_stage_against_oracle(binding, T, R, D, dtype, B, F, hb, h
     m.close()
 
 
+@pytest.mark.parametrize("D,dtype,n_hot", [(64, np.float16, 128), (32, np.float32, 100), (64, np.float32, 37),
+                                            (8, np.float16, 1024), (128, np.float16, 120)])
+def test_hot_row_cache_gives_the_same_pooling(binding, D, dtype, n_hot):
+    """Hot rows served from LDS: same sums as the oracle, with lists that hold
+    duplicates, ids outside the table and ids nobody asks for; one table has
+    no list at all; faults in the looked-up ids are still reported."""
+    say("hot rows", D, dtype.__name__, n_hot)
+    g = np.random.default_rng(51 + D + n_hot)
+    T, R, B, F = 4, 3000, 300, 8
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(dtype) for _ in range(T)]
+    bottom, top = small_mlps(g, F, D, T)
+    # skewed ids so that the lists matter: half of the lookups go to 150 rows
+    lens = g.integers(0, 150, T * B).astype(np.int32)
+    nnz = int(lens.sum())
+    hot_pool = g.permutation(R)[:150]
+    idx = np.where(g.random(nnz) < 0.5, hot_pool[g.integers(0, 150, nnz)], g.integers(0, R, nnz)).astype(np.int32)
+    m = H.make_model(binding, tabs, bottom, top, B, nnz, F)
+    batch = synth.Batch(g.standard_normal((B, F)).astype(np.float32), idx, lens)
+    plain = H.run(m, batch)
+    plain_pooled = m.debug_pooled().cpu().numpy()
+    for t in range(T - 1):                                   # the last table keeps no list
+        ids = hot_pool[g.permutation(150)[:min(n_hot, 150)]].astype(np.int32)
+        extra = np.array([ids[0], R, -5, R + 7, ids[-1]], dtype=np.int32)      # duplicates and bad ids
+        ids = np.concatenate([ids, extra, g.integers(0, R, max(0, n_hot - ids.size - 5)).astype(np.int32)])[:n_hot]
+        m.load_hot_rows(t, ids)
+    hot = H.run(m, batch)
+    assert m.check() == (binding.REC_OK, -1)
+    P, A, nbad, _ = orc.pool(tabs, idx, lens, B, want_abs=True)
+    got = m.debug_pooled().cpu().numpy()
+    H.check_pooled(got, P, A)
+    H.check_pooled(plain_pooled, P, A)
+    off, _, _ = orc.offsets(lens)
+    assert np.array_equal(m.debug_offsets().cpu().numpy().astype(np.int64), off)
+    exact = orc.forward(batch.dense, tabs, idx, lens, bottom, top)
+    mirror = orc.forward(batch.dense, tabs, idx, lens, bottom, top, orc.BF16_MIRROR)
+    H.check_logits(hot, exact["logits"], mirror["logits"])
+    H.run(m, batch)                                          # reproducible
+    assert np.array_equal(got, m.debug_pooled().cpu().numpy())
+    # faults among the looked-up ids are still found, also next to hot ids
+    bad = idx.copy()
+    bad[11] = R + 3
+    bad[5000] = -1
+    H.run(m, synth.Batch(batch.dense, bad, lens))
+    Pb, _, nb, first = orc.pool(tabs, bad, lens, B)
+    assert nb == 2 and m.check() == (binding.REC_ERR_INDEX_RANGE, first)
+    assert np.allclose(m.debug_pooled().cpu().numpy(), Pb, rtol=1e-5, atol=1e-6)
+    # removing the lists returns to the plain kernel, bit for bit
+    for t in range(T):
+        m.load_hot_rows(t, None)
+    again = H.run(m, batch)
+    assert np.array_equal(again, plain) and np.array_equal(m.debug_pooled().cpu().numpy(), plain_pooled)
+    m.close()
+
+
+def test_hot_row_list_limits(binding):
+    say("hot row limits")
+    g = np.random.default_rng(5)
+    tabs = [g.uniform(-1, 1, (50, 64)).astype(np.float32)]          # 256-byte rows
+    bottom, top = small_mlps(g, 4, 64, 1)
+    m = H.make_model(binding, tabs, bottom, top, 4, 100, 4)
+    ids = torch.arange(0, 50, dtype=torch.int32, device="cuda")
+    assert binding.rec_load_hot_rows(m.handle, 0, ids) == binding.REC_OK
+    assert binding.rec_load_hot_rows(m.handle, 1, ids) == binding.REC_ERR_ARG          # table id
+    big = torch.zeros(1025, dtype=torch.int32, device="cuda")
+    assert binding.rec_load_hot_rows(m.handle, 0, big) == binding.REC_ERR_ARG          # > REC_MAX_HOT_ROWS
+    assert binding.rec_load_hot_rows(m.handle, 0, big[:512]) == binding.REC_ERR_ARG    # 128 KB of rows: no fit
+    assert binding.rec_load_hot_rows(m.handle, 0, None) == binding.REC_OK
+    m.close()
+
+
 def test_dense_overlap_does_not_change_results(binding):
     """Bottom-FC on the side stream or in order: same kernels, same bits; and a
     run of back-to-back forwards with different inputs keeps them apart."""
