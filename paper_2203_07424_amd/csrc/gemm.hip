@@ -88,7 +88,7 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
                                                         void *__restrict__ C, int ldc, int vec_ok,
                                                         const float *__restrict__ dot_w,
                                                         const float *__restrict__ dot_bias,
-                                                        float *__restrict__ dot_out)
+                                                        float *__restrict__ dot_out, int grid_n)
 {
     constexpr int WAVES_N = 4 / WAVES_M;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // per-wave tile
@@ -101,7 +101,14 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // Blocks are dealt to the 8 XCDs round-robin.  The 1-D grid is re-ordered so
+    // that XCD x owns the x-th eighth of the tile list (n fastest): the tiles
+    // that share a slab of activations then share an L2 and the slab comes from
+    // HBM once instead of once per XCD.
+    int v = blockIdx.x;
+    if ((gridDim.x & 7) == 0) v = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int bm = v / grid_n, bn = v - bm * grid_n;
+    const int m0 = bm * BM, n0 = bn * BN;
 
     // Staging role: 8 threads cover the 64 k of one row, 32 rows per pass.
     const int ld_row = tid >> 3, ld_chunk = tid & 7;
@@ -240,7 +247,8 @@ struct FcArgs {
 template <int BM, int BN, int WAVES_M, int P>
 hipError_t launch_tile(const FcArgs &a, hipStream_t s)
 {
-    const dim3 grid(a.Npad / BN, (a.M + BM - 1) / BM), block(FC_THREADS);
+    const int grid_n = a.Npad / BN;
+    const dim3 grid(grid_n * ((a.M + BM - 1) / BM)), block(FC_THREADS);
     const __bf16 *Wb = static_cast<const __bf16 *>(a.W);
     // 16-byte loads of fp32 rows need lda % 4 == 0 and an aligned base.
     const int vec_ok = a.a_f32 && (a.lda % 4 == 0) && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0);
@@ -248,7 +256,7 @@ hipError_t launch_tile(const FcArgs &a, hipStream_t s)
 #define REC_FC_LAUNCH(AF, OF, FD)                                                                  \
     hipLaunchKernelGGL((fc_kernel<BM, BN, WAVES_M, P, AF, OF, FD>), grid, block, 0, s, a.A, a.lda, \
                        a.M, a.K, a.Kpad, Wb, a.bias, r, a.C, a.ldc, vec_ok, a.dot_w, a.dot_bias,   \
-                       a.dot_out)
+                       a.dot_out, grid_n)
     if (a.dot_out) {
         if (a.a_f32) REC_FC_LAUNCH(true, false, true);
         else REC_FC_LAUNCH(false, false, true);
@@ -341,12 +349,6 @@ hipError_t launch_fc(const void *A, bool a_f32, int lda, int M, int K, int Kpad,
         if (Npad == 64) return launch_tile<64, 64, 2, 4>(a, s);
         return hipErrorInvalidValue;
     }
-#ifdef REC_FC_FORCE
-    if (REC_FC_FORCE == 1 && Npad % 128 == 0) return launch_tile<128, 128, 2, 2>(a, s);
-    if (REC_FC_FORCE == 2) return launch_tile<64, 64, 2, 4>(a, s);
-    if (REC_FC_FORCE == 3 && Npad % 128 == 0) return launch_tile<32, 128, 1, 4>(a, s);
-    if (REC_FC_FORCE == 4 && Npad % 128 == 0) return launch_tile<64, 128, 1, 4>(a, s);
-#endif
     // Large tiles only where they still give every compute unit a block.
     const long long big_blocks = (long long)(Npad / 128) * ((M + 127) / 128);
     if (Npad % 128 == 0 && big_blocks >= 256) return launch_tile<128, 128, 2, 2>(a, s);

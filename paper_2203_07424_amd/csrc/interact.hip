@@ -25,18 +25,10 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-#ifndef REC_IT_THREADS
-#define REC_IT_THREADS 256
-#endif
-constexpr int IT_THREADS = REC_IT_THREADS;
+constexpr int IT_THREADS = 256;
 constexpr int IT_WAVES = IT_THREADS / 64;
-#ifndef REC_IT_BATCH
-#define REC_IT_BATCH 4
-#endif
-constexpr int IT_BATCH = REC_IT_BATCH;  // 16-byte loads in flight per thread while staging
-#ifndef REC_IT_TILES_PER_WAVE
-#define REC_IT_TILES_PER_WAVE 1
-#endif
+constexpr int IT_BATCH = 4;           // 16-byte loads in flight per thread while staging
+constexpr int IT_TILES_PER_WAVE = 1;  // tiles a wave should get (sets the samples per block)
 
 struct Geometry {
     int V, Vpad, nblk, ntile, d4, ksteps, swmask;
@@ -187,7 +179,7 @@ hipError_t launch_interact(const float *x0, int ldx0, const float *pooled, int B
     // Enough samples per block to give every wave about one tile; small blocks
     // (little LDS each) keep many of them resident, which hides the staging
     // latency of one behind the matrix work of the others.
-    int spb = (REC_IT_TILES_PER_WAVE * IT_WAVES + g.ntile - 1) / g.ntile;
+    int spb = (IT_TILES_PER_WAVE * IT_WAVES + g.ntile - 1) / g.ntile;
     while (spb > 1 && spb * per > 32 * 1024) --spb;
     const dim3 grid((B + spb - 1) / spb), block(IT_THREADS);
     __bf16 *o = static_cast<__bf16 *>(out_bf16);

@@ -17,23 +17,9 @@ namespace rec {
 
 namespace {
 
-#ifndef REC_POOL_WAVES
-#define REC_POOL_WAVES 4
-#endif
-#ifndef REC_POOL_UNROLL
-#define REC_POOL_UNROLL 4
-#endif
-#ifndef REC_POOL_XCD_CHUNKS
-#define REC_POOL_XCD_CHUNKS 1
-#endif
-#ifndef REC_POOL_SAMPLE_MAJOR
-#define REC_POOL_SAMPLE_MAJOR 0
-#endif
-#ifndef REC_POOL_NT
-#define REC_POOL_NT 0
-#endif
-constexpr int POOL_WAVES = REC_POOL_WAVES;    // bags per block
-constexpr int POOL_UNROLL = REC_POOL_UNROLL;  // row loads in flight per lane and step
+// Both were swept on the RMC2-style workload (2..8 loads, 2..8 waves); these are the best.
+constexpr int POOL_WAVES = 4;   // bags per block
+constexpr int POOL_UNROLL = 4;  // row loads in flight per lane and step
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -69,27 +55,18 @@ __global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
     constexpr int D = ROWBYTES / (HALF ? 2 : 4);
 
     const int lane = threadIdx.x & 63;
-#if REC_POOL_XCD_CHUNKS
     // Blocks are handed to the 8 XCDs round-robin; give XCD x the x-th eighth
     // of the (table-major) bag list so that each L2 sees few tables at a time.
     // The grid is a multiple of 8 blocks; surplus blocks fall past nbags.
     const int per = gridDim.x >> 3;
     const int vblk = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
     int bag = vblk * POOL_WAVES + (threadIdx.x >> 6);
-#else
-    int bag = blockIdx.x * POOL_WAVES + (threadIdx.x >> 6);
-#endif
     if (bag >= nbags) return;
     bag = __builtin_amdgcn_readfirstlane(bag);
-#if REC_POOL_SAMPLE_MAJOR
-    const int b = bag / T;
-    const int t = bag - b * T;
-#else
     const int t = bag / B;
     const int b = bag - t * B;
-#endif
-    const int start = offsets[t * B + b];
-    const int end = offsets[t * B + b + 1];
+    const int start = offsets[bag];
+    const int end = offsets[bag + 1];
     const char *base = static_cast<const char *>(tables[t].base);
     const long long rows = tables[t].rows;
 
@@ -101,13 +78,8 @@ __global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
 #pragma unroll
     for (int i = 0; i < NACC; ++i) acc.v[i] = 0.0f;
 
-#if REC_POOL_NT
-#define REC_LOAD_ID(p) __builtin_nontemporal_load(p)
-#else
-#define REC_LOAD_ID(p) (*(p))
-#endif
     int ids = -1;
-    if (start + lane < end) ids = REC_LOAD_ID(indices + start + lane);
+    if (start + lane < end) ids = indices[start + lane];
     for (int k0 = start; k0 < end; k0 += 64) {
         const int n = min(64, end - k0);
         int cur = ids;
@@ -119,7 +91,7 @@ __global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
         }
         // Next 64 ids, requested before the row loads of this step.
         ids = -1;
-        if (k0 + 64 + lane < end) ids = REC_LOAD_ID(indices + k0 + 64 + lane);
+        if (k0 + 64 + lane < end) ids = indices[k0 + 64 + lane];
 
         const int steps = (n + RPW - 1) / RPW;  // wave-wide loads this chunk needs
         for (int j = 0; j < steps; j += POOL_UNROLL) {
@@ -159,10 +131,7 @@ hipError_t launch_lpr(bool half, const TableDesc *tables, int T, int B, const in
                       const int32_t *offsets, float *pooled, ErrRecord *err, hipStream_t s)
 {
     const int nbags = T * B;
-    int blocks = (nbags + POOL_WAVES - 1) / POOL_WAVES;
-#if REC_POOL_XCD_CHUNKS
-    blocks = (blocks + 7) / 8 * 8;
-#endif
+    const int blocks = ((nbags + POOL_WAVES - 1) / POOL_WAVES + 7) / 8 * 8;
     const dim3 grid(blocks), block(POOL_WAVES * 64);
     if (half)
         hipLaunchKernelGGL((pool_kernel<LPR, true>), grid, block, 0, s, tables, indices, offsets,
