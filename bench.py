@@ -203,6 +203,64 @@ def latency_sweep(args) -> int:
     return 0
 
 
+def search_mode(args) -> int:
+    """Gradient-based search (Algorithm 1, accelerator-side P_sp(M+D)) for the
+    batch size and the number of co-located instances with the highest
+    throughput under the SLA; optionally the full grid beside it."""
+    import torch
+    from paper_2203_07424_amd import binding, scheduler, synth
+
+    w0 = synth.WORKLOADS[args.workload]
+    sizes = [int(x) for x in args.sweep_batches.split(",")]
+    counts = list(range(1, args.search_instances + 1))
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t0 = time.time()
+    m0, _, _ = build_model(binding, synth, torch, w0, max(sizes))
+    models = [m0] + [build_model(binding, synth, torch, w0, max(sizes), share_tables=m0)[0]
+                     for _ in counts[1:]]
+    streams = pick_concurrent_streams(torch, dev, len(counts))
+    cdf = synth.zipf_cdf(w0.rows, float(w0.index_dist[1])) if w0.index_dist[0] == "zipf" else None
+    data = {}
+    for B in sizes:
+        w = w0.with_batch(B)
+        outs = [torch.empty(B, dtype=torch.float32, device=dev) for _ in counts]
+        data[B] = []
+        for i in range(2):
+            b = synth.draw_batch(w, 2000 + i, cdf)
+            data[B].append((torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
+                            torch.from_numpy(b.lengths).to(dev), outs))
+    log(f"{len(counts)} instances of {w0.name}, batches {sizes} resident ({time.time() - t0:.1f} s)")
+    memo = {}
+
+    def measure(m, d):
+        if (m, d) not in memo:
+            memo[(m, d)] = scheduler.measure_point(models, streams, data, m, d, rounds=args.sweep_iters)
+            x = memo[(m, d)]
+            log(f"  instances {m} batch {d}: {x.qps / 1e6:.2f} M samples/s, p99 {x.latency_ms:.3f} ms")
+        return memo[(m, d)]
+    res = scheduler.search(measure, counts, sizes, args.sla_ms)
+    grid = None
+    if args.search_exhaustive:
+        grid = [{"instances": m, "batch": d, "samples_per_s": measure(m, d).qps,
+                 "p99_ms": measure(m, d).latency_ms} for m in counts for d in sizes]
+    out = {"metric": f"latency-bounded samples/s per GPU at p99 <= {args.sla_ms} ms, gradient search over "
+                     "(co-located instances, batch size)",
+           "value": res.measurement.qps if res.measurement else None, "unit": "samples/s", "n_gpus": 1,
+           "steps": args.sweep_iters, "warmup": 8,
+           "ms_per_step": res.measurement.latency_ms if res.measurement else None,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f16 tables -> f32 accumulate; bf16 MFMA -> f32 accumulate", "data": "synthetic",
+           "config": {"workload": w0.name, "instances": res.instances, "batch": res.batch,
+                      "sla_ms": args.sla_ms, "points_measured_by_search": res.evaluated,
+                      "grid_points": len(counts) * len(sizes)},
+           "path": res.path, "grid": grid}
+    print(json.dumps(out), flush=True)
+    for mm in models:
+        mm.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -240,6 +298,12 @@ def main() -> int:
     ap.add_argument("--latency-sweep", action="store_true",
                     help="batch-size sweep with per-batch latency percentiles instead of the "
                          "throughput run (meant for --workload rmc2-large)")
+    ap.add_argument("--search", action="store_true",
+                    help="gradient search for (instances, batch size) under --sla-ms instead of "
+                         "the throughput run; batch sizes from --sweep-batches")
+    ap.add_argument("--search-instances", type=int, default=4)
+    ap.add_argument("--search-exhaustive", action="store_true",
+                    help="with --search: also measure every grid point")
     ap.add_argument("--sweep-batches", default="64,256,1024,4096,16384")
     ap.add_argument("--sweep-iters", type=int, default=200)
     ap.add_argument("--sla-ms", type=float, default=20.0)
@@ -249,6 +313,8 @@ def main() -> int:
         return 2
     if args.latency_sweep:
         return latency_sweep(args)
+    if args.search:
+        return search_mode(args)
 
     import numpy as np
     import torch

@@ -450,3 +450,50 @@ def test_large_capacity_variant_sampled_against_oracle(binding):
     H.check_logits(logits[pick], exact["logits"], mirror["logits"])
     m.close()
     torch.cuda.empty_cache()
+
+
+def test_gradient_search_on_measured_throughput(binding):
+    """Algorithm 1 driven by real measurements of the forward pass: every move
+    of the walk raises throughput within the SLA, and the end point is (within
+    measurement noise) the best in-bound point of the fully measured grid."""
+    from oracle import search_oracle as so
+    from paper_2203_07424_amd import scheduler
+    say("gradient search on measured points")
+    w0 = synth.WORKLOADS["tiny"]
+    sizes, counts = [64, 512, 4096], [1, 2, 3]
+    m0, _, _ = H.make_workload_model(binding, w0, max_batch=max(sizes))
+    models = [m0]
+    for _ in counts[1:]:
+        m = binding.RecModel(w0.num_tables, w0.emb_dim, [w0.rows] * w0.num_tables, w0.table_dtype,
+                             w0.num_dense, list(w0.bottom), list(w0.top), max(sizes),
+                             max(sizes) * w0.num_tables * 20)
+        for t in range(w0.num_tables):
+            m.load_table(t, m0.tables[t])
+        H.load_mlps(binding, m, synth.draw_mlp(w0, "bottom"), synth.draw_mlp(w0, "top"))
+        models.append(m)
+    streams = [torch.cuda.Stream() for _ in counts]
+    data = {}
+    for B in sizes:
+        b = synth.draw_batch(w0.with_batch(B), 7)
+        outs = [torch.empty(B, dtype=torch.float32, device="cuda") for _ in counts]
+        data[B] = [(torch.from_numpy(b.dense).cuda(), torch.from_numpy(b.indices).cuda(),
+                    torch.from_numpy(b.lengths).cuda(), outs)]
+    memo = {}
+
+    def measure(m, d):
+        if (m, d) not in memo:
+            memo[(m, d)] = scheduler.measure_point(models, streams, data, m, d, rounds=30, warmup=5)
+        return memo[(m, d)]
+    sla = 50.0
+    res = scheduler.search(measure, counts, sizes, sla)
+    assert res.instances is not None and res.path[0] == (1, 64)
+    for p, q in zip(res.path, res.path[1:]):
+        assert memo[q].qps > memo[p].qps and memo[q].latency_ms < sla
+    tab = lambda i, j: (measure(counts[i], sizes[j]).qps, measure(counts[i], sizes[j]).latency_ms, 0.0)
+    best, best_qps = so.exhaustive(tab, len(counts), len(sizes), sla)
+    got, path = so.algorithm1(tab, len(counts), len(sizes), sla)      # same table, oracle's walk
+    assert [(counts[i], sizes[j]) for i, j in path] == res.path
+    assert res.measurement.qps >= 0.85 * best_qps                     # convexity, up to noise
+    for m in models:
+        assert m.check() == (binding.REC_OK, -1)
+        m.close()
