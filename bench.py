@@ -32,9 +32,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # 1.000), see profiles/pool_rmc2_counters.md.  Valid only for the kernel source
 # the counters were taken with; reported as null once csrc/pool.hip differs.
 POOL_TRAFFIC = {
-    "sha256": "c49be4a068716d219cedf3b3a32fc300e91a6a0b40a9179c618037605bf46205",
-    ("rmc2", 4096): {"fetch_bytes": 554015499.0, "write_bytes": 41943040.0},
-    ("rmc2-uniform", 4096): {"fetch_bytes": 1707529764.0, "write_bytes": 41943188.0},
+    "sha256": "0955c548261b521bd758e15f9ee0244893f62118d175892c30236e6707bc3dc4",
+    ("rmc2", 4096): {"fetch_bytes": 554021144.0, "write_bytes": 41943050.0},
+    ("rmc2-uniform", 4096): {"fetch_bytes": 1707520545.0, "write_bytes": 41943257.0},
 }
 
 
