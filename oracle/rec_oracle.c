@@ -34,6 +34,17 @@
  *   - every layer has a bias;
  *   - an empty bag pools to the zero vector, duplicate ids count with
  *     multiplicity, an id outside [0, rows) contributes zero and is reported.
+ *
+ * Second model shape (Table I, row MT-WnD: 26 tables, one lookup per table,
+ * no pooling, no Bottom-FC, Predict-FC = N towers of 1024-512-256):
+ * oracle_forward_towers().  Readings: the looked-up vectors and the dense
+ * part are concatenated, dense part first, with no interaction operator
+ * (Table I has none for this row); each of the N task towers reads that same
+ * vector, has ReLU on its hidden layers and ends in a linear one-output
+ * layer, one logit per task; the stack of lookups is the general pooled sum,
+ * of which one id per bag is the special case (Sec. VI-B: lookup only, no
+ * Gather-Reduce).  Pins: numpy's concatenate, rows reproduced bit for bit,
+ * tower-wise reduction to single layers, the independent nested-loop forward.
  */
 #include <math.h>
 #include <stddef.h>
@@ -352,5 +363,108 @@ int oracle_forward(const float *dense, const void *const *tables, int dtype,
         memcpy(pooled, P, (size_t)B * T * D * sizeof(double));
 
     free(P); free(h0); free(h1);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* concatenation model with N towers (Table I, MT-WnD row)             */
+/* ------------------------------------------------------------------ */
+
+/*
+ * out[b] = [ x0[b] (w0 values), P[b][0][:], ..., P[b][T-1][:] ],
+ * width w0 + T * D.  No products between the vectors.
+ */
+void oracle_concat(const double *x0, int w0, const double *P, int B, int T,
+                   int D, double *out)
+{
+    int64_t width = w0 + (int64_t)T * D;
+    for (int b = 0; b < B; ++b) {
+        double *o = out + (int64_t)b * width;
+        for (int i = 0; i < w0; ++i)
+            o[i] = x0[(int64_t)b * w0 + i];
+        for (int t = 0; t < T; ++t)
+            for (int d = 0; d < D; ++d)
+                o[w0 + (int64_t)t * D + d] = P[((int64_t)b * T + t) * D + d];
+    }
+}
+
+/*
+ * Forward of the concatenation model.  Inputs as in oracle_forward, except:
+ *   n_bottom may be 0: bottom_widths then has the single entry F and the
+ *     dense part of the concatenation is the dense features themselves;
+ *   the Predict-FC stack exists n_towers times with the same widths
+ *     top_widths (n_top + 1 entries: w0 + T*D ... 1) and its own weights:
+ *     top_W[k * n_top + l] is layer l of tower k.
+ * Outputs (each may be NULL): pooled [B][T][D], bottom_out [B][w0],
+ * concat [B][w0 + T*D], logits [B][n_towers], all fp64.
+ * Returns 0, or -1 on a width chain that does not fit.
+ */
+int oracle_forward_towers(const float *dense, const void *const *tables,
+                          int dtype, const int64_t *rows, int T, int D, int B,
+                          const int32_t *indices, const int32_t *lengths,
+                          int n_bottom, const int32_t *bottom_widths,
+                          const float *const *bottom_W,
+                          const float *const *bottom_b, int n_towers,
+                          int n_top, const int32_t *top_widths,
+                          const float *const *top_W, const float *const *top_b,
+                          int mode, double *pooled, double *bottom_out,
+                          double *concat, double *logits)
+{
+    int w0 = bottom_widths[n_bottom];
+    int64_t width = w0 + (int64_t)T * D;
+    if (n_bottom < 0 || n_towers < 1 || n_top < 1 || top_widths[0] != width ||
+        top_widths[n_top] != 1)
+        return -1;
+
+    int64_t maxw = width;
+    for (int i = 0; i <= n_bottom; ++i)
+        if (bottom_widths[i] > maxw) maxw = bottom_widths[i];
+    for (int i = 0; i <= n_top; ++i)
+        if (top_widths[i] > maxw) maxw = top_widths[i];
+
+    double *P = (double *)malloc((size_t)B * T * D * sizeof(double));
+    double *h0 = (double *)malloc((size_t)B * maxw * sizeof(double));
+    double *h1 = (double *)malloc((size_t)B * maxw * sizeof(double));
+    double *z = (double *)malloc((size_t)B * width * sizeof(double));
+
+    oracle_pool(tables, dtype, rows, T, D, B, indices, lengths, P, NULL, NULL);
+
+    int F = bottom_widths[0];
+    for (int64_t i = 0; i < (int64_t)B * F; ++i)
+        h0[i] = (double)dense[i];
+    for (int l = 0; l < n_bottom; ++l) {
+        oracle_fc(h0, bottom_W[l], bottom_b[l], B, bottom_widths[l],
+                  bottom_widths[l + 1], 1, mode, h1);
+        double *tmp = h0; h0 = h1; h1 = tmp;
+    }
+    if (bottom_out)
+        memcpy(bottom_out, h0, (size_t)B * w0 * sizeof(double));
+
+    oracle_concat(h0, w0, P, B, T, D, z);
+    /* What the towers' matrix units are fed with: the mirror narrows it here. */
+    if (mode == ORACLE_BF16_MIRROR)
+        for (int64_t i = 0; i < (int64_t)B * width; ++i)
+            z[i] = oracle_round_bf16(z[i]);
+    if (concat)
+        memcpy(concat, z, (size_t)B * width * sizeof(double));
+
+    for (int k = 0; k < n_towers; ++k) {
+        memcpy(h0, z, (size_t)B * width * sizeof(double));
+        for (int l = 0; l < n_top; ++l) {
+            int last = l + 1 == n_top;
+            /* the one-output layer is a dot product: never narrowed */
+            oracle_fc(h0, top_W[k * n_top + l], top_b[k * n_top + l], B,
+                      top_widths[l], top_widths[l + 1], !last,
+                      last ? ORACLE_EXACT : mode, h1);
+            double *tmp = h0; h0 = h1; h1 = tmp;
+        }
+        if (logits)
+            for (int b = 0; b < B; ++b)
+                logits[(int64_t)b * n_towers + k] = h0[b];
+    }
+    if (pooled)
+        memcpy(pooled, P, (size_t)B * T * D * sizeof(double));
+
+    free(P); free(h0); free(h1); free(z);
     return 0;
 }

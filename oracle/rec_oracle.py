@@ -183,3 +183,62 @@ def forward(dense: np.ndarray, tables: Sequence[np.ndarray], indices: np.ndarray
     if rc != 0:
         raise ValueError("layer widths do not fit the model")
     return out
+
+
+def concat(x0: np.ndarray, P: np.ndarray) -> np.ndarray:
+    x0 = np.ascontiguousarray(x0, dtype=np.float64)
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    B, T, D = P.shape
+    w0 = x0.shape[1]
+    assert x0.shape == (B, w0)
+    out = np.empty((B, w0 + T * D), dtype=np.float64)
+    lib().oracle_concat(_p(x0), C.c_int(w0), _p(P), C.c_int(B), C.c_int(T), C.c_int(D), _p(out))
+    return out
+
+
+def forward_towers(dense: np.ndarray, tables: Sequence[np.ndarray], indices: np.ndarray,
+                   lengths: np.ndarray, bottom: List[Tuple[np.ndarray, np.ndarray]],
+                   towers: List[List[Tuple[np.ndarray, np.ndarray]]], mode: int = EXACT) -> dict:
+    """Concatenation model with len(towers) Predict-FC towers (`bottom` may be
+    empty).  Returns pooled, bottom_out, concat, logits [B, n_towers] (fp64)."""
+    dense = np.ascontiguousarray(dense, dtype=np.float32)
+    tables = [np.ascontiguousarray(t) for t in tables]
+    indices = np.ascontiguousarray(indices, dtype=np.int32)
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    B, F = dense.shape
+    T, D = len(tables), tables[0].shape[1]
+    assert lengths.size == T * B and int(np.maximum(lengths, 0).sum()) == indices.size
+    rows = np.array([t.shape[0] for t in tables], dtype=np.int64)
+
+    def widths(layers, first):
+        w = [first] + [L[0].shape[0] for L in layers]
+        for i, (W, b) in enumerate(layers):
+            assert W.shape == (w[i + 1], w[i]) and b.shape == (w[i + 1],)
+        return np.array(w, dtype=np.int32)
+
+    bw = widths(bottom, F)
+    w0 = int(bw[-1])
+    width = w0 + T * D
+    tw = widths(towers[0], towers[0][0][0].shape[1])
+    for tower in towers:
+        assert len(tower) == len(towers[0]) and np.array_equal(widths(tower, int(tw[0])), tw)
+    bW = [np.ascontiguousarray(W, dtype=np.float32) for W, _ in bottom]
+    bb = [np.ascontiguousarray(b, dtype=np.float32) for _, b in bottom]
+    tW = [np.ascontiguousarray(W, dtype=np.float32) for tower in towers for W, _ in tower]
+    tb = [np.ascontiguousarray(b, dtype=np.float32) for tower in towers for _, b in tower]
+    out = {
+        "pooled": np.empty((B, T, D), dtype=np.float64),
+        "bottom_out": np.empty((B, w0), dtype=np.float64),
+        "concat": np.empty((B, width), dtype=np.float64),
+        "logits": np.empty((B, len(towers)), dtype=np.float64),
+    }
+    rc = lib().oracle_forward_towers(
+        _p(dense), _ptr_array(tables), C.c_int(_dtype_code(tables)), _p(rows),
+        C.c_int(T), C.c_int(D), C.c_int(B), _p(indices), _p(lengths),
+        C.c_int(len(bottom)), _p(bw), _ptr_array(bW), _ptr_array(bb),
+        C.c_int(len(towers)), C.c_int(len(towers[0])), _p(tw), _ptr_array(tW), _ptr_array(tb),
+        C.c_int(mode), _p(out["pooled"]), _p(out["bottom_out"]), _p(out["concat"]),
+        _p(out["logits"]))
+    if rc != 0:
+        raise ValueError("layer widths do not fit the model")
+    return out

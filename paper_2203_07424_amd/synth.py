@@ -8,7 +8,8 @@ sharing any computation.
 
 The workloads stand in for the production models of Table I (DLRM-RMC1/2/3:
 about 10 or 100 embedding tables of 1M-20M rows, 20-160 or 20-50 lookups per
-table with pooling, Bottom-FC / Predict-FC stacks) and for the production
+table with pooling, Bottom-FC / Predict-FC stacks; MT-WnD: 26 tables, one
+lookup each, no Bottom-FC, N Predict-FC towers) and for the production
 query traces of Sec. II-A (variable pooling factors, Fig. 2(c)); neither is
 public, so shapes follow Table I and values are drawn here.
 
@@ -59,13 +60,17 @@ class Workload:
     num_dense: int
     pooling: Tuple               # ("fixed", L) | ("poisson", mean, lo, hi)
     index_dist: Tuple            # ("uniform",) | ("zipf", alpha)
-    bottom: Tuple[int, ...]      # widths F, ..., D
-    top: Tuple[int, ...]         # widths D + T(T+1)/2, ..., 1
+    bottom: Tuple[int, ...]      # widths F, ..., D; (F,) alone = no Bottom-FC
+    top: Tuple[int, ...]         # widths interact_width, ..., 1
     seed: int = MASTER_SEED
+    interaction: str = "dot"     # "dot": pairwise dots | "concat": plain concatenation
+    towers: int = 1              # Predict-FC stacks (tasks), each of widths `top`
 
     @property
     def interact_width(self) -> int:
         t = self.num_tables
+        if self.interaction == "concat":
+            return self.bottom[-1] + t * self.emb_dim
         return self.emb_dim + t * (t + 1) // 2
 
     def with_batch(self, batch: int) -> "Workload":
@@ -97,6 +102,16 @@ WORKLOADS: Dict[str, Workload] = {
     "rmc2-large": Workload("rmc2-large", 60, 20_000_000, 64, "f16", 4096, 256,
                            ("poisson", 80.0, 1, 200), ("zipf", 1.2),
                            (256, 256, 64), (_tri(60, 64), 512, 128, 1)),
+    # MT-WnD-style (Table I row MT-WnD, "small" 1M-row tables): one lookup per
+    # table, no pooling, no Bottom-FC, no interaction, 4 task towers.
+    "mtwnd": Workload("mtwnd", 26, 1_000_000, 64, "f16", 4096, 64, ("fixed", 1),
+                      ("zipf", 1.05), (64,), (64 + 26 * 64, 1024, 512, 256, 1),
+                      interaction="concat", towers=4),
+    # The same shape shrunk to what a CPU check finishes in seconds, with
+    # ragged widths and a Bottom-FC layer.
+    "mtwnd-tiny": Workload("mtwnd-tiny", 5, 50_000, 32, "f32", 200, 24, ("fixed", 1),
+                           ("uniform",), (24, 40), (40 + 5 * 32, 96, 72, 1),
+                           interaction="concat", towers=3),
 }
 
 
@@ -218,15 +233,15 @@ def draw_dense(w: Workload, batch_id: int) -> np.ndarray:
     return g.standard_normal((w.batch, w.num_dense), dtype=np.float32)
 
 
-def draw_mlp(w: Workload, which: str) -> List[Tuple[np.ndarray, np.ndarray]]:
+def draw_mlp(w: Workload, which: str, tower: int = 0) -> List[Tuple[np.ndarray, np.ndarray]]:
     """Master fp32 weights [out, in] and biases [out], both ~ N(0, 1/fan_in)
-    (variance 1/fan_in), for the "bottom" or "top" stack."""
+    (variance 1/fan_in), for the "bottom" stack or tower `tower` of the "top" one."""
     widths = w.bottom if which == "bottom" else w.top
     base = 0 if which == "bottom" else 100
     layers = []
     for i in range(len(widths) - 1):
         fan_in, fan_out = widths[i], widths[i + 1]
-        g = _rng(w.seed, "weights", base + i)
+        g = _rng(w.seed, "weights", base + i, tower)
         std = np.float32(fan_in ** -0.5)
         W = g.standard_normal((fan_out, fan_in), dtype=np.float32) * std
         b = g.standard_normal(fan_out, dtype=np.float32) * std

@@ -389,3 +389,111 @@ def test_threads_do_not_change_results():
     orc.set_threads(1)
     for key in a:
         assert np.array_equal(a[key], b[key])
+
+
+# ------------------------------------------------------------------ concatenation model, N towers
+def _toy_towers(g, T=3, R=7, D=4, B=4, bottom=(5,), hidden=(6, 3), n_towers=3, dtype=np.float32,
+                one_lookup=False):
+    tabs = [g.uniform(-1, 1, (R, D)).astype(dtype) for _ in range(T)]
+    lens = (np.ones(T * B) if one_lookup else g.integers(0, 4, T * B)).astype(np.int32)
+    idx = g.integers(0, R, int(lens.sum())).astype(np.int32)
+    dense = g.standard_normal((B, bottom[0])).astype(np.float32)
+    def stack(widths):
+        return [(g.standard_normal((widths[i + 1], widths[i])).astype(np.float32),
+                 g.standard_normal(widths[i + 1]).astype(np.float32))
+                for i in range(len(widths) - 1)]
+    topw = (bottom[-1] + T * D,) + tuple(hidden) + (1,)
+    return dense, tabs, idx, lens, stack(bottom), [stack(topw) for _ in range(n_towers)]
+
+
+def test_concat_is_numpy_concatenate():
+    g = rng(30)
+    x0 = g.standard_normal((5, 3))
+    P = g.standard_normal((5, 4, 6))
+    assert np.array_equal(orc.concat(x0, P), np.concatenate([x0, P.reshape(5, 24)], axis=1))
+
+
+@pytest.mark.parametrize("seed,dtype,bottom", [(31, np.float32, (5,)), (32, np.float16, (5, 6, 3)),
+                                               (33, np.float32, (2, 4))])
+def test_towers_forward_matches_nested_loop_python(seed, dtype, bottom):
+    g = rng(seed)
+    dense, tabs, idx, lens, bot, towers = _toy_towers(g, dtype=dtype, bottom=bottom)
+    got = orc.forward_towers(dense, tabs, idx, lens, bot, towers)
+    want = bruteforce.forward_towers(dense.tolist(), [t.tolist() for t in tabs], idx.tolist(), lens.tolist(),
+                                     [(W.tolist(), b.tolist()) for W, b in bot],
+                                     [[(W.tolist(), b.tolist()) for W, b in tw] for tw in towers])
+    assert np.allclose(got["concat"], np.array(want["concat"]), rtol=1e-12, atol=1e-12)
+    assert np.allclose(got["logits"], np.array(want["logits"]), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_towers_one_lookup_reproduces_rows_bit_for_bit(dtype):
+    # One id per bag: no reduction happens, the concatenation holds the stored rows.
+    g = rng(34)
+    dense, tabs, idx, lens, bot, towers = _toy_towers(g, T=4, R=11, D=8, B=5, dtype=dtype, one_lookup=True)
+    got = orc.forward_towers(dense, tabs, idx, lens, bot, towers)
+    T, B, D, w0 = 4, 5, 8, 5
+    assert np.array_equal(got["concat"][:, :w0], dense.astype(np.float64))   # no Bottom-FC: dense as given
+    for t in range(T):
+        for b in range(B):
+            row = tabs[t][idx[t * B + b]].astype(np.float64)
+            assert np.array_equal(got["concat"][b, w0 + t * D:w0 + (t + 1) * D], row)
+
+
+def test_towers_reduce_to_single_layers_and_are_independent():
+    g = rng(35)
+    dense, tabs, idx, lens, bot, towers = _toy_towers(g, bottom=(5, 4), n_towers=3)
+    got = orc.forward_towers(dense, tabs, idx, lens, bot, towers)
+    # every tower is the plain layer chain applied to the same concatenated vector
+    z = got["concat"]
+    for k, tw in enumerate(towers):
+        h = z
+        for i, (W, b) in enumerate(tw):
+            h = h @ W.astype(np.float64).T + b.astype(np.float64)
+            if i + 1 < len(tw):
+                h = np.maximum(h, 0.0)
+        assert np.allclose(got["logits"][:, k], h[:, 0], rtol=1e-12, atol=1e-12)
+    # permuting the towers permutes the columns; a single tower gives its column
+    perm = [2, 0, 1]
+    got_p = orc.forward_towers(dense, tabs, idx, lens, bot, [towers[k] for k in perm])
+    assert np.array_equal(got_p["logits"], got["logits"][:, perm])
+    one = orc.forward_towers(dense, tabs, idx, lens, bot, [towers[1]])
+    assert np.array_equal(one["logits"][:, 0], got["logits"][:, 1])
+    # equal weights, equal logits; zero weights, the last bias
+    same = orc.forward_towers(dense, tabs, idx, lens, bot, [towers[0], towers[0]])
+    assert np.array_equal(same["logits"][:, 0], same["logits"][:, 1])
+    zero = [[(np.zeros_like(W), b) for W, b in tw] for tw in towers]
+    zl = orc.forward_towers(dense, tabs, idx, lens, bot, zero)["logits"]
+    assert np.array_equal(zl, np.tile([float(tw[-1][1][0]) for tw in zero], (4, 1)))
+
+
+def test_towers_steps_compose_and_mirror_narrows_matrix_layers_only():
+    g = rng(36)
+    dense, tabs, idx, lens, bot, towers = _toy_towers(g, bottom=(5, 6), n_towers=2)
+    P, _, _, _ = orc.pool(tabs, idx, lens, 4)
+    for mode in (orc.EXACT, orc.BF16_MIRROR):
+        got = orc.forward_towers(dense, tabs, idx, lens, bot, towers, mode)
+        assert np.array_equal(got["pooled"], P)
+        h = dense.astype(np.float64)
+        for W, b in bot:
+            h = orc.fc(h, W, b, True, mode)
+        assert np.array_equal(got["bottom_out"], h)
+        z = orc.concat(h, P)
+        if mode == orc.BF16_MIRROR:
+            z = np.vectorize(orc.round_bf16)(z)
+        assert np.array_equal(got["concat"], z)
+        for k, tw in enumerate(towers):
+            y = z
+            for i, (W, b) in enumerate(tw):
+                last = i + 1 == len(tw)
+                y = orc.fc(y, W, b, not last, orc.EXACT if last else mode)
+            assert np.array_equal(got["logits"][:, k], y[:, 0])
+
+
+def test_towers_reject_bad_width_chain():
+    g = rng(37)
+    dense, tabs, idx, lens, bot, towers = _toy_towers(g)
+    bad = [[(np.zeros((3, 9), np.float32), np.zeros(3, np.float32)),
+            (np.zeros((1, 3), np.float32), np.zeros(1, np.float32))]]
+    with pytest.raises(ValueError):
+        orc.forward_towers(dense, tabs, idx, lens, bot, bad)

@@ -8,8 +8,11 @@ from paper_2203_07424_amd import synth
 
 def test_workload_shapes_follow_the_interaction_width():
     for w in synth.WORKLOADS.values():
-        assert w.bottom[0] == w.num_dense and w.bottom[-1] == w.emb_dim
+        assert w.bottom[0] == w.num_dense
+        assert w.interaction == "concat" or w.bottom[-1] == w.emb_dim
         assert w.top[0] == w.interact_width and w.top[-1] == 1
+    assert synth.WORKLOADS["mtwnd"].top[0] == 64 + 26 * 64 and synth.WORKLOADS["mtwnd"].towers == 4
+    assert synth.WORKLOADS["mtwnd-tiny"].top[0] == 40 + 5 * 32
     assert synth.WORKLOADS["tiny"].top[0] == 68
     assert synth.WORKLOADS["rmc1"].top[0] == 119
     assert synth.WORKLOADS["rmc2"].top[0] == 884
@@ -88,6 +91,14 @@ def test_batch_is_reproducible_and_consistent():
     W, bias = synth.draw_mlp(w, "bottom")[0]
     assert W.shape == (256, 13) and bias.shape == (256,)
     assert abs(W.std() - 13 ** -0.5) < 0.02
+    # towers draw from streams of their own; tower 0 is the single-stack stream
+    m = synth.WORKLOADS["mtwnd-tiny"]
+    t0, t1 = synth.draw_mlp(m, "top", 0), synth.draw_mlp(m, "top", 1)
+    assert t0[0][0].shape == (96, 200) and not np.array_equal(t0[0][0], t1[0][0])
+    assert np.array_equal(t0[0][0], synth.draw_mlp(m, "top")[0][0])
+    assert synth.draw_mlp(synth.WORKLOADS["mtwnd"], "bottom") == []
+    one = synth.draw_batch(m, 0)
+    assert one.nnz == 5 * 200 and (one.lengths == 1).all()
 
 
 def test_slice_and_compaction_keep_bag_contents():
