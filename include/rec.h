@@ -15,6 +15,13 @@
  *               (pairwise-dot interaction of the DLRM model the paper cites)
  *   logit     = Predict-FC(z)                     (DenseNet, Table I)
  *
+ * A second model shape (Table I, row MT-WnD: one lookup per table, no pooling,
+ * no Bottom-FC, N Predict-FC towers) has no interaction operator:
+ *
+ *   z         = [x0, pooled_0, ..., pooled_{T-1}]     (x0 = dense when there is
+ *                                                      no Bottom-FC)
+ *   logit_k   = tower_k(z), k = 0..N-1                (one logit per task)
+ *
  * Bottom-FC runs independently of the SparseNet and Predict-FC waits for both
  * (Sec. III-A).  Element-wise work (bias, ReLU, narrowing, concatenation) is
  * fused into the producing kernels (Sec. IV-A, operator fusion).
@@ -57,15 +64,26 @@ typedef enum {
 
 typedef enum { REC_F32 = 0, REC_F16 = 1 } rec_dtype;
 
-/* Which stack a layer belongs to. */
+/* Which stack a layer belongs to: REC_BOTTOM, or REC_TOP + k for tower k of the
+ * Predict-FC (REC_TOP alone when there is one stack). */
 enum { REC_BOTTOM = 0, REC_TOP = 1 };
+
+/* How the dense part and the pooled vectors become the Predict-FC input. */
+enum {
+    REC_INTERACT_DOT = 0,    /* [x0, pairwise dots]: DLRM-RMC rows of Table I        */
+    REC_INTERACT_CONCAT = 1  /* [x0, pooled vectors]: MT-WnD row of Table I          */
+};
+
+/* Most Predict-FC towers a model can have. */
+#define REC_MAX_TOWERS 8
 
 /* Intermediate buffers rec_debug_get() can expose (all inside the workspace). */
 enum {
     REC_DBG_OFFSETS = 0,   /* int32 [T*B + 1], table-major                       */
-    REC_DBG_POOLED = 1,    /* fp32  [B][T][D]                                    */
-    REC_DBG_BOTTOM_OUT = 2,/* fp32  [B][D]                                       */
-    REC_DBG_INTERACT = 3   /* bf16  [B][ld], ld = *ld_out; columns >= width are 0 */
+    REC_DBG_POOLED = 1,    /* fp32  [B][T][D]; REC_INTERACT_DOT only             */
+    REC_DBG_BOTTOM_OUT = 2,/* fp32  [B][ld]; models with a Bottom-FC only        */
+    REC_DBG_INTERACT = 3   /* bf16  [B][ld], ld = *ld_out; columns >= width are 0:
+                              the Predict-FC input of either model shape          */
 };
 
 /* Stages timed by rec_set_profiling(). */
@@ -78,10 +96,17 @@ enum {
  * Model shape (Table I columns: # of Embs, Emb Size, Bottom-FC, Predict-FC).
  *   rows[t]         rows of table t, each < 2^31
  *   emb_dim         D; D * sizeof(element) must be 16 * 2^k bytes, k = 0..6
- *   bottom_widths   n_bottom + 1 entries: num_dense, ..., emb_dim
- *   top_widths      n_top + 1 entries: emb_dim + T(T+1)/2, ..., 1
+ *   bottom_widths   n_bottom + 1 entries: num_dense, ..., w0.  n_bottom = 0
+ *                   (one entry) means no Bottom-FC: x0 is the dense input.
+ *                   REC_INTERACT_DOT needs w0 = emb_dim.
+ *   top_widths      n_top + 1 entries, the first being the width of z:
+ *                   emb_dim + T(T+1)/2 (REC_INTERACT_DOT) or w0 + T * emb_dim
+ *                   (REC_INTERACT_CONCAT), the last being 1
  *   max_batch       largest batch rec_forward() will be given
  *   max_nnz         largest total number of ids per batch, < 2^31
+ *   interaction     REC_INTERACT_*
+ *   num_towers      Predict-FC stacks of widths top_widths, each with weights
+ *                   of its own, all reading the same z; 0 counts as 1
  * The arrays are copied; they need not outlive rec_create().
  */
 typedef struct {
@@ -96,11 +121,14 @@ typedef struct {
     const int32_t *top_widths;
     int32_t max_batch;
     int64_t max_nnz;
+    int32_t interaction;
+    int32_t num_towers;
 } rec_config;
 
 /* Validates the shape and builds the host-side model.  No device work.
- * REC_ERR_ARG (null / non-positive counts), REC_ERR_SHAPE (width chain,
- * emb_dim), REC_ERR_OVERFLOW (rows, max_nnz or T*max_batch >= 2^31). */
+ * REC_ERR_ARG (null / non-positive counts, bad enum, more than REC_MAX_TOWERS
+ * towers), REC_ERR_SHAPE (width chain, emb_dim), REC_ERR_OVERFLOW (rows,
+ * max_nnz or T*max_batch >= 2^31). */
 REC_API rec_status rec_create(const rec_config *cfg, rec_model **out);
 
 /* Frees the host-side model.  Device buffers stay the caller's. */
@@ -140,8 +168,8 @@ REC_API rec_status rec_load_hot_rows(rec_model *m, int32_t table, const int32_t 
  * followed by fp32 bias); 0 on a bad layer id. */
 REC_API size_t rec_mlp_packed_bytes(const rec_model *m, int32_t which, int32_t layer);
 
-/* Packs layer `layer` of stack `which`: dev_W is fp32 [out][in] row-major,
- * dev_b fp32 [out]; dev_packed (256-byte aligned, rec_mlp_packed_bytes()) receives
+/* Packs layer `layer` of stack `which` (REC_BOTTOM, or REC_TOP + tower):
+ * dev_W is fp32 [out][in] row-major, dev_b fp32 [out]; dev_packed (256-byte aligned, rec_mlp_packed_bytes()) receives
  * the weights rounded to bf16 (nearest even) and zero padded.  Enqueued on
  * `stream`; dev_W / dev_b may be released once the stream has passed it,
  * dev_packed is borrowed for the life of the model. */
@@ -153,7 +181,7 @@ REC_API rec_status rec_load_mlp(rec_model *m, int32_t which, int32_t layer, cons
  *   dev_dense    fp32  [batch][num_dense]
  *   dev_indices  int32 [nnz], bags concatenated table-major
  *   dev_lengths  int32 [num_tables * batch], entry t*batch + b = bag (t, b)
- *   dev_logits   fp32  [batch]  (pre-sigmoid)
+ *   dev_logits   fp32  [batch][num_towers]  (pre-sigmoid)
  * No allocation, no synchronisation, no host read of device data.
  * Host-checkable faults return at once: REC_ERR_ARG (null, batch < 0 or
  * > max_batch, nnz < 0 or > max_nnz), REC_ERR_STATE (workspace, a table or a

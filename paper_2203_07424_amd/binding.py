@@ -26,7 +26,9 @@ REC_OK = 0
 REC_ERR_ARG, REC_ERR_SHAPE, REC_ERR_STATE, REC_ERR_LENGTHS = 1, 2, 3, 4
 REC_ERR_INDEX_RANGE, REC_ERR_OVERFLOW, REC_ERR_DEVICE = 5, 6, 7
 REC_F32, REC_F16 = 0, 1
-REC_BOTTOM, REC_TOP = 0, 1
+REC_BOTTOM, REC_TOP = 0, 1          # REC_TOP + k: tower k of the Predict-FC
+REC_INTERACT_DOT, REC_INTERACT_CONCAT = 0, 1
+REC_MAX_TOWERS = 8
 REC_DBG_OFFSETS, REC_DBG_POOLED, REC_DBG_BOTTOM_OUT, REC_DBG_INTERACT = 0, 1, 2, 3
 REC_OPT_OVERLAP_DENSE = 0
 REC_NUM_STAGES = 5
@@ -44,7 +46,7 @@ class rec_config(C.Structure):
                 ("num_dense", C.c_int32), ("n_bottom", C.c_int32),
                 ("bottom_widths", C.POINTER(C.c_int32)), ("n_top", C.c_int32),
                 ("top_widths", C.POINTER(C.c_int32)), ("max_batch", C.c_int32),
-                ("max_nnz", C.c_int64)]
+                ("max_nnz", C.c_int64), ("interaction", C.c_int32), ("num_towers", C.c_int32)]
 
 
 _vp = C.c_void_p
@@ -107,12 +109,13 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 # Raw entry points, same names as the C boundary; each returns the status.
 def rec_create(num_tables: int, emb_dim: int, rows: Sequence[int], table_dtype: int,
                num_dense: int, bottom_widths: Sequence[int], top_widths: Sequence[int],
-               max_batch: int, max_nnz: int) -> Tuple[int, Optional[int]]:
+               max_batch: int, max_nnz: int, interaction: int = REC_INTERACT_DOT,
+               num_towers: int = 1) -> Tuple[int, Optional[int]]:
     rows_a = (C.c_int64 * len(rows))(*rows)
     bw = (C.c_int32 * len(bottom_widths))(*bottom_widths)
     tw = (C.c_int32 * len(top_widths))(*top_widths)
     cfg = rec_config(num_tables, emb_dim, rows_a, table_dtype, num_dense, len(bottom_widths) - 1,
-                     bw, len(top_widths) - 1, tw, max_batch, max_nnz)
+                     bw, len(top_widths) - 1, tw, max_batch, max_nnz, interaction, num_towers)
     out = _vp()
     st = _lib.rec_create(C.byref(cfg), C.byref(out))
     return st, out.value
@@ -191,7 +194,8 @@ class RecModel:
 
     def __init__(self, num_tables: int, emb_dim: int, rows: Sequence[int], table_dtype: str,
                  num_dense: int, bottom_widths: Sequence[int], top_widths: Sequence[int],
-                 max_batch: int, max_nnz: int, device: str = "cuda:0"):
+                 max_batch: int, max_nnz: int, device: str = "cuda:0", interaction: str = "dot",
+                 towers: int = 1):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the forward pass has no CPU path")
         self.device = torch.device(device)
@@ -199,9 +203,12 @@ class RecModel:
         self.table_dtype = {"f32": torch.float32, "f16": torch.float16}[table_dtype]
         self.width = top_widths[0]
         self.n_bottom, self.n_top = len(bottom_widths) - 1, len(top_widths) - 1
+        self.towers, self.w0 = towers, bottom_widths[-1]
         code = REC_F16 if table_dtype == "f16" else REC_F32
+        inter = {"dot": REC_INTERACT_DOT, "concat": REC_INTERACT_CONCAT}[interaction]
         st, self.handle = rec_create(num_tables, emb_dim, list(rows), code, num_dense,
-                                     list(bottom_widths), list(top_widths), max_batch, max_nnz)
+                                     list(bottom_widths), list(top_widths), max_batch, max_nnz,
+                                     inter, towers)
         if st != REC_OK:
             raise RecError(st, "rec_create")
         self.ws = torch.empty(rec_workspace_bytes(self.handle), dtype=torch.uint8, device=self.device)
@@ -251,9 +258,11 @@ class RecModel:
 
     def forward(self, dense: torch.Tensor, indices: torch.Tensor, lengths: torch.Tensor,
                 logits: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Returns fp32 logits: [batch] for one Predict-FC stack, [batch, towers] for several."""
         batch = dense.shape[0]
         if logits is None:
-            logits = torch.empty(batch, dtype=torch.float32, device=self.device)
+            shape = (batch,) if self.towers == 1 else (batch, self.towers)
+            logits = torch.empty(shape, dtype=torch.float32, device=self.device)
         self._ok(rec_forward(self.handle, dense, indices, lengths, batch, indices.numel(), logits),
                  "rec_forward")
         self.last_batch = batch
@@ -293,10 +302,10 @@ class RecModel:
         B = self.last_batch
         st, p, ld = rec_debug_get(self.handle, REC_DBG_BOTTOM_OUT)
         raw, ld = self._view(REC_DBG_BOTTOM_OUT, 4 * B * ld)
-        return raw.view(torch.float32).view(B, ld)[:, :self.D].clone()
+        return raw.view(torch.float32).view(B, ld)[:, :self.w0].clone()
 
     def debug_interact(self) -> torch.Tensor:
-        """bf16 [B, ld]; columns beyond the interaction width are zero padding."""
+        """The Predict-FC input, bf16 [B, ld]; columns beyond its width are zero padding."""
         B = self.last_batch
         st, p, ld = rec_debug_get(self.handle, REC_DBG_INTERACT)
         raw, ld = self._view(REC_DBG_INTERACT, 2 * B * ld)

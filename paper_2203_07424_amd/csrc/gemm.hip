@@ -14,6 +14,11 @@
 // A block of 4 waves computes a BM x BN tile; tiles of A and W go through one
 // LDS buffer each, the next tile's global loads being in flight while the
 // current one is multiplied.
+//
+// Several stacks of equal shape (the N task towers of Table I's MT-WnD row)
+// run as one launch: the tile list is the tiles of stack 0, then stack 1, ...;
+// a block picks its stack's weights from a table passed by value and offsets
+// its activation pointers by the stack's column block.
 #include "rec_internal.h"
 
 namespace rec {
@@ -81,14 +86,13 @@ __device__ inline void load_a_chunk(AChunk<false> &c, const void *A, long long r
 // the epilogue contracts act(C) with a weight vector - the one-output last
 // layer - and writes one fp32 logit per row.
 template <int BM, int BN, int WAVES_M, int P, bool A_F32, bool OUT_F32, bool FUSE_DOT>
-__global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__ A, int lda, int M,
-                                                        int K, int Kpad,
-                                                        const __bf16 *__restrict__ W,
-                                                        const float *__restrict__ bias, int relu,
-                                                        void *__restrict__ C, int ldc, int vec_ok,
-                                                        const float *__restrict__ dot_w,
-                                                        const float *__restrict__ dot_bias,
-                                                        float *__restrict__ dot_out, int grid_n)
+__global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__ A0, int lda,
+                                                        long long a_stride, int M, int K, int Kpad,
+                                                        const FcGroups groups, int relu,
+                                                        void *__restrict__ C0, int ldc,
+                                                        long long c_stride, int vec_ok,
+                                                        float *__restrict__ dot_out, int dot_ld,
+                                                        int grid_n, int tiles_per_group)
 {
     constexpr int WAVES_N = 4 / WAVES_M;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // per-wave tile
@@ -107,8 +111,16 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
     // HBM once instead of once per XCD.
     int v = blockIdx.x;
     if ((gridDim.x & 7) == 0) v = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int grp = v / tiles_per_group;
+    v -= grp * tiles_per_group;
     const int bm = v / grid_n, bn = v - bm * grid_n;
     const int m0 = bm * BM, n0 = bn * BN;
+    const void *A = static_cast<const char *>(A0) + grp * a_stride * (A_F32 ? 4 : 2);
+    void *C = static_cast<char *>(C0) + grp * c_stride * (OUT_F32 ? 4 : 2);
+    const __bf16 *__restrict__ W = static_cast<const __bf16 *>(groups.W[grp]);
+    const float *__restrict__ bias = groups.bias[grp];
+    const float *__restrict__ dot_w = groups.dot_w[grp];
+    const float *__restrict__ dot_bias = groups.dot_bias[grp];
 
     // Staging role: 8 threads cover the 64 k of one row, 32 rows per pass.
     const int ld_row = tid >> 3, ld_chunk = tid & 7;
@@ -232,31 +244,25 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
             float d = dot_bias[0];
 #pragma unroll
             for (int w = 0; w < WAVES_N; ++w) d += red[w * BM + tid];
-            dot_out[m0 + tid] = d;
+            dot_out[(long long)(m0 + tid) * dot_ld + grp] = d;
         }
     }
 }
 
-struct FcArgs {
-    const void *A; bool a_f32; int lda, M, K, Kpad;
-    const void *W; const float *bias; int Npad; bool relu;
-    void *C; bool out_f32; int ldc;
-    const float *dot_w, *dot_bias; float *dot_out;  // non-null dot_out: fused one-output layer
-};
-
 template <int BM, int BN, int WAVES_M, int P>
-hipError_t launch_tile(const FcArgs &a, hipStream_t s)
+hipError_t launch_tile(const FcProblem &a, hipStream_t s)
 {
     const int grid_n = a.Npad / BN;
-    const dim3 grid(grid_n * ((a.M + BM - 1) / BM)), block(FC_THREADS);
-    const __bf16 *Wb = static_cast<const __bf16 *>(a.W);
-    // 16-byte loads of fp32 rows need lda % 4 == 0 and an aligned base.
-    const int vec_ok = a.a_f32 && (a.lda % 4 == 0) && (reinterpret_cast<uintptr_t>(a.A) % 16 == 0);
+    const int tiles = grid_n * ((a.M + BM - 1) / BM);
+    const dim3 grid(tiles * a.groups), block(FC_THREADS);
+    // 16-byte loads of fp32 rows need lda and the stack stride % 4 == 0 and an aligned base.
+    const int vec_ok = a.a_f32 && (a.lda % 4 == 0) && (a.a_stride % 4 == 0) &&
+                       (reinterpret_cast<uintptr_t>(a.A) % 16 == 0);
     const int r = a.relu ? 1 : 0;
 #define REC_FC_LAUNCH(AF, OF, FD)                                                                  \
     hipLaunchKernelGGL((fc_kernel<BM, BN, WAVES_M, P, AF, OF, FD>), grid, block, 0, s, a.A, a.lda, \
-                       a.M, a.K, a.Kpad, Wb, a.bias, r, a.C, a.ldc, vec_ok, a.dot_w, a.dot_bias,   \
-                       a.dot_out, grid_n)
+                       a.a_stride, a.M, a.K, a.Kpad, a.g, r, a.C, a.ldc, a.c_stride, vec_ok,       \
+                       a.dot_out, a.dot_ld, grid_n, tiles)
     if (a.dot_out) {
         if (a.a_f32) REC_FC_LAUNCH(true, false, true);
         else REC_FC_LAUNCH(false, false, true);
@@ -272,11 +278,15 @@ hipError_t launch_tile(const FcArgs &a, hipStream_t s)
 // fp32 weights; 8 lanes share a row.  The input is the previous layer's fp32
 // output, or the bf16 interaction output when the stack has a single layer.
 template <bool A_F32>
-__global__ __launch_bounds__(256) void rowdot_kernel(const void *__restrict__ A, int lda, int M,
-                                                     int Kpad, const float *__restrict__ w,
-                                                     const float *__restrict__ bias,
-                                                     float *__restrict__ logits)
+__global__ __launch_bounds__(256) void rowdot_kernel(const void *__restrict__ A0, int lda,
+                                                     long long a_stride, int M, int Kpad,
+                                                     const FcGroups groups,
+                                                     float *__restrict__ logits, int ld)
 {
+    const int grp = blockIdx.y;
+    const void *A = static_cast<const char *>(A0) + grp * a_stride * (A_F32 ? 4 : 2);
+    const float *__restrict__ w = groups.dot_w[grp];
+    const float *__restrict__ bias = groups.dot_bias[grp];
     const int sub = threadIdx.x & 7;
     const long long m = (long long)blockIdx.x * 32 + (threadIdx.x >> 3);
     const long long row = m < M ? m : M - 1;
@@ -305,7 +315,7 @@ __global__ __launch_bounds__(256) void rowdot_kernel(const void *__restrict__ A,
     acc += __shfl_xor(acc, 1, 64);
     acc += __shfl_xor(acc, 2, 64);
     acc += __shfl_xor(acc, 4, 64);
-    if (sub == 0 && m < M) logits[m] = acc + bias[0];
+    if (sub == 0 && m < M) logits[m * ld + grp] = acc + bias[0];
 }
 
 // One-output layer: fp32 weights [Kpad], zero padded, and its bias.
@@ -336,36 +346,38 @@ __global__ __launch_bounds__(256) void pack_fc_kernel(const float *__restrict__ 
 
 bool fc_can_fuse_dot(int Npad) { return Npad == 64 || Npad == 128; }
 
-hipError_t launch_fc(const void *A, bool a_f32, int lda, int M, int K, int Kpad, const void *W,
-                     const float *bias, int Npad, bool relu, void *C, bool out_f32, int ldc,
-                     const float *dot_w, const float *dot_bias, float *dot_out, hipStream_t s)
+hipError_t launch_fc(const FcProblem &a, hipStream_t s)
 {
+    const int M = a.M, Npad = a.Npad;
     if (M <= 0) return hipSuccess;
-    if (Kpad % BK != 0 || Npad % 64 != 0) return hipErrorInvalidValue;
-    const FcArgs a{A, a_f32, lda, M, K, Kpad, W, bias, Npad, relu, C, out_f32, ldc, dot_w, dot_bias, dot_out};
-    if (dot_out) {
+    if (a.Kpad % BK != 0 || Npad % 64 != 0 || a.groups < 1 || a.groups > MAX_GROUPS)
+        return hipErrorInvalidValue;
+    if (a.dot_out) {
         // The block must own whole rows.
         if (Npad == 128) return launch_tile<32, 128, 1, 4>(a, s);
         if (Npad == 64) return launch_tile<64, 64, 2, 4>(a, s);
         return hipErrorInvalidValue;
     }
     // Large tiles only where they still give every compute unit a block.
-    const long long big_blocks = (long long)(Npad / 128) * ((M + 127) / 128);
+    const long long big_blocks = (long long)a.groups * (Npad / 128) * ((M + 127) / 128);
     if (Npad % 128 == 0 && big_blocks >= 256) return launch_tile<128, 128, 2, 2>(a, s);
-    const long long mid_blocks = (long long)(Npad / 64) * ((M + 63) / 64);
+    const long long mid_blocks = (long long)a.groups * (Npad / 64) * ((M + 63) / 64);
     if (Npad % 128 == 0 && mid_blocks < 256) return launch_tile<32, 128, 1, 4>(a, s);
     return launch_tile<64, 64, 2, 4>(a, s);
 }
 
-hipError_t launch_rowdot(const void *A, bool a_f32, int lda, int M, int Kpad, const float *w,
-                         const float *bias, float *logits, hipStream_t s)
+hipError_t launch_rowdot(const void *A, bool a_f32, int lda, long long a_stride, int M, int Kpad,
+                         const FcGroups &groups, int n_groups, float *logits, int ld, hipStream_t s)
 {
     if (M <= 0) return hipSuccess;
-    const dim3 grid((M + 31) / 32), block(256);
+    if (n_groups < 1 || n_groups > MAX_GROUPS) return hipErrorInvalidValue;
+    const dim3 grid((M + 31) / 32, n_groups), block(256);
     if (a_f32)
-        hipLaunchKernelGGL(rowdot_kernel<true>, grid, block, 0, s, A, lda, M, Kpad, w, bias, logits);
+        hipLaunchKernelGGL(rowdot_kernel<true>, grid, block, 0, s, A, lda, a_stride, M, Kpad, groups,
+                           logits, ld);
     else
-        hipLaunchKernelGGL(rowdot_kernel<false>, grid, block, 0, s, A, lda, M, Kpad, w, bias, logits);
+        hipLaunchKernelGGL(rowdot_kernel<false>, grid, block, 0, s, A, lda, a_stride, M, Kpad, groups,
+                           logits, ld);
     return hipGetLastError();
 }
 

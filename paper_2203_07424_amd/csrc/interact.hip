@@ -1,4 +1,5 @@
-// S3: pairwise-dot feature interaction and concatenation.
+// S3: pairwise-dot feature interaction and concatenation (and, at the end, the
+// dense part of the plain-concatenation model, which has no interaction).
 //
 // Per sample, the T pooled vectors and the Bottom-FC output x0 form
 // X = [x0; pooled_0; ...; pooled_{T-1}]  (V = T + 1 rows of D).  The Predict-FC
@@ -160,6 +161,25 @@ __global__ __launch_bounds__(IT_THREADS) void interact_kernel(const float *__res
                 *reinterpret_cast<const u32x4 *>(sO + s * ldo + 8 * c);
 }
 
+// Concatenation model (no interaction operator): the dense part of each
+// Predict-FC input row, narrowed, and the zero padding behind the row.
+__global__ __launch_bounds__(256) void concat_dense_kernel(const float *__restrict__ x0, int ldx0, int w0,
+                                                           int B, __bf16 *__restrict__ z, int width,
+                                                           int ldz)
+{
+    const int per_row = w0 + (ldz - width);
+    const long long total = (long long)B * per_row;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long b = i / per_row;
+        const int c = (int)(i - b * per_row);
+        if (c < w0)
+            z[b * ldz + c] = (__bf16)x0[b * ldx0 + c];
+        else
+            z[b * ldz + width + (c - w0)] = (__bf16)0.0f;
+    }
+}
+
 }  // namespace
 
 size_t interact_lds_bytes_per_sample(int T, int D)
@@ -191,6 +211,17 @@ hipError_t launch_interact(const float *x0, int ldx0, const float *pooled, int B
     case 128: hipLaunchKernelGGL(interact_kernel<8>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
     default: hipLaunchKernelGGL(interact_kernel<0>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_concat_dense(const float *x0, int ldx0, int w0, int B, void *z_bf16, int width,
+                               int ldz, hipStream_t s)
+{
+    const long long total = (long long)B * (w0 + ldz - width);
+    if (total <= 0) return hipSuccess;
+    const int blocks = (int)((total + 255) / 256 < 2048 ? (total + 255) / 256 : 2048);
+    hipLaunchKernelGGL(concat_dense_kernel, dim3(blocks), dim3(256), 0, s, x0, ldx0, w0, B,
+                       static_cast<__bf16 *>(z_bf16), width, ldz);
     return hipGetLastError();
 }
 

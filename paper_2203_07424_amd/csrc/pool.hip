@@ -9,6 +9,14 @@
 // shuffle, keeps several row loads in flight, accumulates in fp32 and folds the
 // RPW partial sums in a fixed order, so results do not vary from run to run.
 // The work is pure random-gather traffic: HBM bandwidth bounds it.
+//
+// Bags of a few ids (one lookup per table and no pooling, Table I row MT-WnD)
+// would leave most of such a wave idle: pool_short_kernel gives each group of
+// LPR lanes a bag of its own, RPW bags per wave.
+//
+// In the concatenation model the sums go, narrowed to bf16, straight into the
+// Predict-FC input row of their sample (concatenation and conversion fused,
+// Sec. IV-A) instead of the fp32 pooled buffer.
 #include <hip/hip_fp16.h>
 
 #include "rec_internal.h"
@@ -21,8 +29,13 @@ namespace {
 constexpr int POOL_WAVES = 4;   // bags per block
 constexpr int POOL_UNROLL = 4;  // row loads in flight per lane and step
 
+constexpr int SHORT_UNROLL = 4;  // row loads in flight per lane in the short-bag kernel
+constexpr int SHORT_MEAN = 4;    // mean ids per bag up to which bags share a wave
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 template <bool HALF>
 struct Acc {
@@ -43,10 +56,44 @@ __device__ inline void accumulate(Acc<HALF> &a, const f32x4 raw, bool ok)
     }
 }
 
-template <int LPR, bool HALF>
+// The NACC sums a lane holds (columns chunk * NACC ... of bag (t, b)) to where they belong.
+template <bool HALF, bool CONCAT>
+__device__ inline void store_sums(const Acc<HALF> &acc, const PoolOut &out, int vec_ok, int b, int t,
+                                  int T, int D, int chunk)
+{
+    constexpr int NACC = HALF ? 8 : 4;
+    if (CONCAT) {
+        __bf16 *o = static_cast<__bf16 *>(out.z) + (long long)b * out.ldz + out.col0 + t * D + chunk * NACC;
+        if (vec_ok) {
+            if (HALF) {
+                bf16x8 v;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = (__bf16)acc.v[i];
+                *reinterpret_cast<bf16x8 *>(o) = v;
+            } else {
+                bf16x4 v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (__bf16)acc.v[i];
+                *reinterpret_cast<bf16x4 *>(o) = v;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NACC; ++i) o[i] = (__bf16)acc.v[i];
+        }
+    } else {
+        float *o = out.pooled + ((long long)b * T + t) * D + chunk * NACC;
+#pragma unroll
+        for (int i = 0; i < NACC; i += 4) {
+            f32x4 v = {acc.v[i], acc.v[i + 1], acc.v[i + 2], acc.v[i + 3]};
+            *reinterpret_cast<f32x4 *>(o + i) = v;
+        }
+    }
+}
+
+template <int LPR, bool HALF, bool CONCAT>
 __global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
     const TableDesc *__restrict__ tables, const int32_t *__restrict__ indices,
-    const int32_t *__restrict__ offsets, float *__restrict__ pooled, int B, int T, int nbags,
+    const int32_t *__restrict__ offsets, const PoolOut out, int vec_ok, int B, int T, int nbags,
     ErrRecord *err)
 {
     constexpr int RPW = 64 / LPR;
@@ -116,49 +163,116 @@ __global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
 #pragma unroll
         for (int i = 0; i < NACC; ++i) acc.v[i] += __shfl_xor(acc.v[i], m, 64);
     }
-    if (sub == 0) {
-        float *out = pooled + ((long long)b * T + t) * D + chunk * NACC;
+    if (sub == 0) store_sums<HALF, CONCAT>(acc, out, vec_ok, b, t, T, D, chunk);
+}
+
+// One bag per group of LPR lanes.  Lanes past the last bag work on a copy of it
+// and store nothing.
+template <int LPR, bool HALF, bool CONCAT>
+__global__ __launch_bounds__(POOL_WAVES * 64) void pool_short_kernel(
+    const TableDesc *__restrict__ tables, const int32_t *__restrict__ indices,
+    const int32_t *__restrict__ offsets, const PoolOut out, int vec_ok, int B, int T, int nbags,
+    ErrRecord *err)
+{
+    constexpr int RPW = 64 / LPR;
+    constexpr int ROWBYTES = LPR * 16;
+    constexpr int NACC = HALF ? 8 : 4;
+    constexpr int D = ROWBYTES / (HALF ? 2 : 4);
+
+    const int lane = threadIdx.x & 63;
+    const int sub = lane / LPR, chunk = lane % LPR;
+    const int per = gridDim.x >> 3;
+    const int vblk = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    const long long slot = ((long long)vblk * POOL_WAVES + (threadIdx.x >> 6)) * RPW + sub;
+    const bool live = slot < nbags;
+    const int bag = live ? (int)slot : nbags - 1;
+    const int t = bag / B;
+    const int b = bag - t * B;
+    const int start = offsets[bag];
+    const int end = live ? offsets[bag + 1] : start;
+    const char *lane_base = static_cast<const char *>(tables[t].base) + chunk * 16;
+    const long long rows = tables[t].rows;
+
+    Acc<HALF> acc;
 #pragma unroll
-        for (int i = 0; i < NACC; i += 4) {
-            f32x4 o = {acc.v[i], acc.v[i + 1], acc.v[i + 2], acc.v[i + 3]};
-            *reinterpret_cast<f32x4 *>(out + i) = o;
+    for (int i = 0; i < NACC; ++i) acc.v[i] = 0.0f;
+
+    for (int k0 = start; k0 < end; k0 += SHORT_UNROLL) {
+        f32x4 raw[SHORT_UNROLL];
+        bool ok[SHORT_UNROLL];
+#pragma unroll
+        for (int u = 0; u < SHORT_UNROLL; ++u) {
+            const int k = k0 + u;
+            const int id = indices[k < end ? k : end - 1];
+            ok[u] = k < end;
+            if (ok[u] && (unsigned long long)(long long)id >= (unsigned long long)rows) {
+                if (chunk == 0) {
+                    atomicMin(&err->first_bad_idx, (unsigned long long)k);
+                    atomicOr(&err->flags, ERR_INDEX_RANGE);
+                }
+                ok[u] = false;
+            }
+            const long long row = ok[u] ? id : 0;
+            raw[u] = *reinterpret_cast<const f32x4 *>(lane_base + row * ROWBYTES);
         }
+#pragma unroll
+        for (int u = 0; u < SHORT_UNROLL; ++u) accumulate<HALF>(acc, raw[u], ok[u]);
     }
+    if (live) store_sums<HALF, CONCAT>(acc, out, vec_ok, b, t, T, D, chunk);
+}
+
+template <int LPR, bool HALF, bool CONCAT>
+hipError_t launch_shape(bool short_bags, const TableDesc *tables, int T, int B, const int32_t *indices,
+                        const int32_t *offsets, const PoolOut &out, ErrRecord *err, hipStream_t s)
+{
+    constexpr int NACC = HALF ? 8 : 4;
+    const int nbags = T * B;
+    const int vec_ok = CONCAT && out.col0 % NACC == 0 && reinterpret_cast<uintptr_t>(out.z) % 16 == 0;
+    const dim3 block(POOL_WAVES * 64);
+    if (short_bags) {
+        const int per_block = POOL_WAVES * (64 / LPR);
+        const dim3 grid(((nbags + per_block - 1) / per_block + 7) / 8 * 8);
+        hipLaunchKernelGGL((pool_short_kernel<LPR, HALF, CONCAT>), grid, block, 0, s, tables, indices,
+                           offsets, out, vec_ok, B, T, nbags, err);
+    } else {
+        const dim3 grid(((nbags + POOL_WAVES - 1) / POOL_WAVES + 7) / 8 * 8);
+        hipLaunchKernelGGL((pool_kernel<LPR, HALF, CONCAT>), grid, block, 0, s, tables, indices, offsets,
+                           out, vec_ok, B, T, nbags, err);
+    }
+    return hipGetLastError();
 }
 
 template <int LPR>
-hipError_t launch_lpr(bool half, const TableDesc *tables, int T, int B, const int32_t *indices,
-                      const int32_t *offsets, float *pooled, ErrRecord *err, hipStream_t s)
+hipError_t launch_lpr(bool half, bool short_bags, const TableDesc *tables, int T, int B,
+                      const int32_t *indices, const int32_t *offsets, const PoolOut &out, ErrRecord *err,
+                      hipStream_t s)
 {
-    const int nbags = T * B;
-    const int blocks = ((nbags + POOL_WAVES - 1) / POOL_WAVES + 7) / 8 * 8;
-    const dim3 grid(blocks), block(POOL_WAVES * 64);
-    if (half)
-        hipLaunchKernelGGL((pool_kernel<LPR, true>), grid, block, 0, s, tables, indices, offsets,
-                           pooled, B, T, nbags, err);
-    else
-        hipLaunchKernelGGL((pool_kernel<LPR, false>), grid, block, 0, s, tables, indices, offsets,
-                           pooled, B, T, nbags, err);
-    return hipGetLastError();
+    if (out.z) {
+        if (half) return launch_shape<LPR, true, true>(short_bags, tables, T, B, indices, offsets, out, err, s);
+        return launch_shape<LPR, false, true>(short_bags, tables, T, B, indices, offsets, out, err, s);
+    }
+    if (half) return launch_shape<LPR, true, false>(short_bags, tables, T, B, indices, offsets, out, err, s);
+    return launch_shape<LPR, false, false>(short_bags, tables, T, B, indices, offsets, out, err, s);
 }
 
 }  // namespace
 
 hipError_t launch_pool(const TableDesc *tables, int dtype, int T, int D, int B,
-                       const int32_t *indices, const int32_t *offsets, float *pooled,
+                       const int32_t *indices, const int32_t *offsets, PoolOut out, long long nnz,
                        ErrRecord *err, hipStream_t s)
 {
     if (T <= 0 || B <= 0) return hipSuccess;
     const bool half = dtype == REC_F16;
     const int rowbytes = D * (half ? 2 : 4);
+    const bool sh = rowbytes < 1024 && nnz <= (long long)SHORT_MEAN * T * B;
     switch (rowbytes / 16) {
-    case 1: return launch_lpr<1>(half, tables, T, B, indices, offsets, pooled, err, s);
-    case 2: return launch_lpr<2>(half, tables, T, B, indices, offsets, pooled, err, s);
-    case 4: return launch_lpr<4>(half, tables, T, B, indices, offsets, pooled, err, s);
-    case 8: return launch_lpr<8>(half, tables, T, B, indices, offsets, pooled, err, s);
-    case 16: return launch_lpr<16>(half, tables, T, B, indices, offsets, pooled, err, s);
-    case 32: return launch_lpr<32>(half, tables, T, B, indices, offsets, pooled, err, s);
-    case 64: return launch_lpr<64>(half, tables, T, B, indices, offsets, pooled, err, s);
+    case 1: return launch_lpr<1>(half, sh, tables, T, B, indices, offsets, out, err, s);
+    case 2: return launch_lpr<2>(half, sh, tables, T, B, indices, offsets, out, err, s);
+    case 4: return launch_lpr<4>(half, sh, tables, T, B, indices, offsets, out, err, s);
+    case 8: return launch_lpr<8>(half, sh, tables, T, B, indices, offsets, out, err, s);
+    case 16: return launch_lpr<16>(half, sh, tables, T, B, indices, offsets, out, err, s);
+    case 32: return launch_lpr<32>(half, sh, tables, T, B, indices, offsets, out, err, s);
+    case 64: return launch_lpr<64>(half, sh, tables, T, B, indices, offsets, out, err, s);
     default: return hipErrorInvalidValue;
     }
 }

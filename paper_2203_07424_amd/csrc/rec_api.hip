@@ -1,5 +1,7 @@
 // C boundary of the forward pass: model bookkeeping on the host and the fixed
-// launch sequence  scan -> pool -> Bottom-FC -> interaction -> Predict-FC.
+// launch sequence  scan -> pool -> Bottom-FC -> interaction -> Predict-FC
+// (interaction = pairwise dots, or plain concatenation for the MT-WnD shape of
+// Table I, whose Predict-FC is N towers run side by side).
 // Bottom-FC does not depend on the SparseNet and Predict-FC waits for both
 // (Sec. III-A); on one in-order stream that dependency is the launch order.
 #include <algorithm>
@@ -28,6 +30,10 @@ struct Layer {
 
 struct rec_model {
     int T = 0, D = 0, F = 0, dtype = REC_F32;
+    int interaction = REC_INTERACT_DOT;
+    int towers = 1, n_top = 0;  // top holds towers * n_top layers, tower-major
+    int w0 = 0;                 // width of the dense part x0 of the Predict-FC input
+    int z_width = 0;            // width of the Predict-FC input
     int max_batch = 0;
     long long max_nnz = 0;
     std::vector<long long> rows;
@@ -42,7 +48,7 @@ struct rec_model {
     int z_ld = 0;            // padded width of the interaction output (act[0])
     int act_ld = 0;          // widest padded hidden activation row (elements), act[1], act[2]
     size_t act_row_bytes = 0;  // bytes of one activation row: bf16 everywhere, fp32 into the dot layer
-    int d_pad = 0;
+    int x0_ld = 0;           // row stride of the Bottom-FC output in the workspace
     char *ws = nullptr;
 
     // Bottom-FC runs on a stream of the library's own, beside scan and pooling.
@@ -74,10 +80,13 @@ bool all_loaded(const rec_model *m)
 
 Layer *find_layer(rec_model *m, int which, int layer)
 {
-    if (which != REC_BOTTOM && which != REC_TOP) return nullptr;
-    std::vector<Layer> &v = which == REC_BOTTOM ? m->bottom : m->top;
-    if (layer < 0 || layer >= (int)v.size()) return nullptr;
-    return &v[layer];
+    if (which == REC_BOTTOM) {
+        if (layer < 0 || layer >= (int)m->bottom.size()) return nullptr;
+        return &m->bottom[layer];
+    }
+    const int tower = which - REC_TOP;
+    if (tower < 0 || tower >= m->towers || layer < 0 || layer >= m->n_top) return nullptr;
+    return &m->top[(size_t)tower * m->n_top + layer];
 }
 
 }  // namespace
@@ -104,10 +113,14 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     if (!out) return REC_ERR_ARG;
     *out = nullptr;
     if (!cfg || !cfg->rows || !cfg->bottom_widths || !cfg->top_widths) return REC_ERR_ARG;
-    if (cfg->num_tables <= 0 || cfg->emb_dim <= 0 || cfg->num_dense <= 0 || cfg->n_bottom <= 0 ||
+    if (cfg->num_tables <= 0 || cfg->emb_dim <= 0 || cfg->num_dense <= 0 || cfg->n_bottom < 0 ||
         cfg->n_top <= 0 || cfg->max_batch <= 0 || cfg->max_nnz < 0)
         return REC_ERR_ARG;
     if (cfg->table_dtype != REC_F32 && cfg->table_dtype != REC_F16) return REC_ERR_ARG;
+    if (cfg->interaction != REC_INTERACT_DOT && cfg->interaction != REC_INTERACT_CONCAT) return REC_ERR_ARG;
+    if (cfg->num_towers < 0 || cfg->num_towers > REC_MAX_TOWERS) return REC_ERR_ARG;
+    const int towers = cfg->num_towers > 0 ? cfg->num_towers : 1;
+    const bool concat = cfg->interaction == REC_INTERACT_CONCAT;
 
     const int T = cfg->num_tables, D = cfg->emb_dim;
     // A row must be 16 * 2^k bytes (k = 0..6) for the 128-bit gather.
@@ -123,42 +136,49 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     if (cfg->max_nnz >= (1ll << 31)) return REC_ERR_OVERFLOW;
     if ((long long)T * cfg->max_batch >= (1ll << 31)) return REC_ERR_OVERFLOW;
 
-    const long long width = D + (long long)T * (T + 1) / 2;
-    if (width >= (1ll << 24)) return REC_ERR_OVERFLOW;
-    if (cfg->bottom_widths[0] != cfg->num_dense || cfg->bottom_widths[cfg->n_bottom] != D)
-        return REC_ERR_SHAPE;
-    if (cfg->top_widths[0] != width || cfg->top_widths[cfg->n_top] != 1) return REC_ERR_SHAPE;
     for (int i = 0; i <= cfg->n_bottom; ++i)
         if (cfg->bottom_widths[i] <= 0 || cfg->bottom_widths[i] >= (1 << 24)) return REC_ERR_SHAPE;
     for (int i = 0; i <= cfg->n_top; ++i)
         if (cfg->top_widths[i] <= 0 || cfg->top_widths[i] >= (1 << 24)) return REC_ERR_SHAPE;
-    if (interact_lds_bytes_per_sample(T, D) > 64 * 1024) return REC_ERR_SHAPE;
+    const int w0 = cfg->bottom_widths[cfg->n_bottom];
+    const long long width = concat ? w0 + (long long)T * D : D + (long long)T * (T + 1) / 2;
+    if (width >= (1ll << 24)) return REC_ERR_OVERFLOW;
+    if (cfg->bottom_widths[0] != cfg->num_dense || (!concat && w0 != D)) return REC_ERR_SHAPE;
+    if (cfg->top_widths[0] != width || cfg->top_widths[cfg->n_top] != 1) return REC_ERR_SHAPE;
+    if (!concat && interact_lds_bytes_per_sample(T, D) > 64 * 1024) return REC_ERR_SHAPE;
 
     rec_model *m = new (std::nothrow) rec_model();
     if (!m) return REC_ERR_ARG;
     m->T = T; m->D = D; m->F = cfg->num_dense; m->dtype = cfg->table_dtype;
+    m->interaction = cfg->interaction; m->towers = towers; m->n_top = cfg->n_top;
+    m->w0 = w0; m->z_width = (int)width;
     m->max_batch = cfg->max_batch; m->max_nnz = cfg->max_nnz;
     m->rows.assign(cfg->rows, cfg->rows + T);
     m->table_loaded.assign(T, 0);
     m->desc.assign(T, TableDesc{nullptr, 0, nullptr, 0, 0});
     for (int t = 0; t < T; ++t) m->desc[t].rows = cfg->rows[t];
-    m->d_pad = pad_up(D);
+    m->x0_ld = pad_up(w0);
     m->z_ld = pad_up((int)width);
     m->act_ld = PAD;
-    auto fill = [&](std::vector<Layer> &v, const int32_t *w, int n) {
-        v.resize(n);
+    // Hidden activations of the towers sit side by side in one row.
+    auto fill = [&](Layer *v, const int32_t *w, int n, int side_by_side) {
         for (int i = 0; i < n; ++i) {
             v[i].K = w[i]; v[i].N = w[i + 1];
             v[i].Kpad = pad_up(w[i]); v[i].Npad = pad_up(w[i + 1]);
-            if (v[i].Npad > m->act_ld) m->act_ld = v[i].Npad;
+            if (i + 1 < n || side_by_side == 1)  // the one-output layer leaves no activation row
+                m->act_ld = std::max(m->act_ld, side_by_side * v[i].Npad);
         }
     };
-    fill(m->bottom, cfg->bottom_widths, cfg->n_bottom);
-    fill(m->top, cfg->top_widths, cfg->n_top);
-    m->top.back().dot = true;
+    m->bottom.resize(cfg->n_bottom);
+    fill(m->bottom.data(), cfg->bottom_widths, cfg->n_bottom, 1);
+    m->top.resize((size_t)towers * cfg->n_top);
+    for (int k = 0; k < towers; ++k) {
+        fill(&m->top[(size_t)k * cfg->n_top], cfg->top_widths, cfg->n_top, towers);
+        m->top[(size_t)k * cfg->n_top + cfg->n_top - 1].dot = true;
+    }
     m->act_row_bytes = 2 * (size_t)m->act_ld;
-    if (m->top.size() > 1)  // the layer feeding the dot leaves fp32
-        m->act_row_bytes = std::max(m->act_row_bytes, sizeof(float) * m->top[m->top.size() - 2].Npad);
+    if (cfg->n_top > 1)  // the layer feeding the dot leaves fp32
+        m->act_row_bytes = std::max(m->act_row_bytes, sizeof(float) * towers * m->top[cfg->n_top - 2].Npad);
 
     const size_t nb = (size_t)T * m->max_batch;
     size_t o = 0;
@@ -166,9 +186,9 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     m->off_tables = o;    o += align_up(sizeof(TableDesc) * T);
     m->off_offsets = o;   o += align_up(sizeof(int32_t) * (nb + 1));
     m->off_tile_sums = o; o += align_up(sizeof(long long) * ((nb + SCAN_TILE - 1) / SCAN_TILE));
-    m->off_pooled = o;    o += align_up(sizeof(float) * nb * D);
-    m->off_x0 = o;        o += align_up(sizeof(float) * (size_t)m->max_batch * m->d_pad);
-    // act[0] holds the interaction output (kept for inspection); the hidden
+    m->off_pooled = o;    o += concat ? 0 : align_up(sizeof(float) * nb * D);
+    m->off_x0 = o;        o += cfg->n_bottom > 0 ? align_up(sizeof(float) * (size_t)m->max_batch * m->x0_ld) : 0;
+    // act[0] holds the Predict-FC input (kept for inspection); the hidden
     // activations of both stacks alternate between act[1] and act[2].
     m->off_act[0] = o; o += align_up(2 * (size_t)m->max_batch * m->z_ld);
     m->off_act[1] = o; o += align_up((size_t)m->max_batch * m->act_row_bytes);
@@ -285,10 +305,13 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int B = batch, T = m->T, D = m->D;
+    const bool concat = m->interaction == REC_INTERACT_CONCAT;
     ErrRecord *err = m->at<ErrRecord>(m->off_err);
     int32_t *offsets = m->at<int32_t>(m->off_offsets);
     float *pooled = m->at<float>(m->off_pooled);
-    float *x0 = m->at<float>(m->off_x0);
+    // Without a Bottom-FC the dense part of the Predict-FC input is the dense input.
+    const float *x0 = m->bottom.empty() ? dev_dense : m->at<float>(m->off_x0);
+    const int x0_ld = m->bottom.empty() ? m->F : m->x0_ld;
     void *act[3] = {m->at<void>(m->off_act[0]), m->at<void>(m->off_act[1]),
                     m->at<void>(m->off_act[2])};
     // Forward number i is timed when i is a multiple of the period; it is the
@@ -308,22 +331,24 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
 
     // S2 does not depend on S0/S1: with overlap it is enqueued on the side
     // stream, forked from and joined back into the caller's stream.
-    const bool overlap = m->overlap_dense;
+    const bool overlap = m->overlap_dense && !m->bottom.empty();
     hipStream_t sd = overlap ? m->side : s;
     auto bottom_fc = [&]() -> hipError_t {
         // ReLU after every layer; the last one leaves fp32 for the interaction.
-        const void *in = dev_dense;
-        int ld_in = m->F;
-        bool in_f32 = true;
+        FcProblem p{};
+        p.A = dev_dense; p.a_f32 = true; p.lda = m->F;
+        p.M = B; p.relu = true; p.groups = 1;
         for (size_t i = 0; i < m->bottom.size(); ++i) {
             const Layer &l = m->bottom[i];
             const bool last = i + 1 == m->bottom.size();
-            void *dst = last ? static_cast<void *>(x0) : act[1 + (i & 1)];
-            const int ldc = last ? m->d_pad : m->act_ld;
-            const hipError_t e = launch_fc(in, in_f32, ld_in, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true,
-                                           dst, last, ldc, nullptr, nullptr, nullptr, sd);
+            p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
+            p.g.W[0] = l.W; p.g.bias[0] = l.bias;
+            p.C = last ? static_cast<void *>(m->at<float>(m->off_x0)) : act[1 + (i & 1)];
+            p.out_f32 = last;
+            p.ldc = last ? m->x0_ld : m->act_ld;
+            const hipError_t e = launch_fc(p, sd);
             if (e != hipSuccess) return e;
-            in = dst; ld_in = ldc; in_f32 = false;
+            p.A = p.C; p.lda = p.ldc; p.a_f32 = false;
         }
         return hipSuccess;
     };
@@ -338,11 +363,12 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
     // S0
     REC_TRY(launch_scan(dev_lengths, T * B, nnz, offsets, m->at<long long>(m->off_tile_sums), err, s));
     REC_MARK();
-    // S1: with hot lists registered, hot rows are served from LDS.
+    // S1: with hot lists registered, hot rows are served from LDS.  In the
+    // concatenation model the sums go straight into the Predict-FC input rows.
     {
         int hmax = 0;
         for (const TableDesc &d : m->desc) hmax = d.n_hot > hmax ? d.n_hot : hmax;
-        if (hmax > 0) {
+        if (hmax > 0 && !concat) {
             // Capacity: at least the longest list; a sparse hash (128 slots of rows
             // or more, where LDS allows) keeps the per-wave probe chains short.
             const int rowbytes = D * (m->dtype == REC_F16 ? 2 : 4);
@@ -352,8 +378,10 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
             REC_TRY(launch_pool_hot(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
                                     pooled, hcap, m->num_cus, err, s));
         } else {
+            const PoolOut out = concat ? PoolOut{nullptr, act[0], m->z_ld, m->w0}
+                                       : PoolOut{pooled, nullptr, 0, 0};
             REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
-                                pooled, err, s));
+                                out, nnz, err, s));
         }
     }
     REC_MARK();
@@ -364,33 +392,50 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         REC_TRY(bottom_fc());
     REC_MARK();
     // S3 -> act[0], row stride z_ld, zero filled up to it
-    REC_TRY(launch_interact(x0, m->d_pad, pooled, B, T, D, act[0], m->z_ld, s));
+    if (concat)
+        REC_TRY(launch_concat_dense(x0, x0_ld, m->w0, B, act[0], m->z_width, m->z_ld, s));
+    else
+        REC_TRY(launch_interact(x0, x0_ld, pooled, B, T, D, act[0], m->z_ld, s));
     REC_MARK();
-    // S4: ReLU on all layers but the last.  The last layer is one fp32 dot per
-    // sample: folded into the epilogue of the layer before it when that layer's
-    // block tile spans whole rows, else that layer leaves fp32 for a dot kernel.
+    // S4: the towers run side by side, their hidden activations in adjacent
+    // column blocks of one row.  ReLU on all layers but the last.  The last layer
+    // is one fp32 dot per sample and tower: folded into the epilogue of the layer
+    // before it when that layer's block tile spans whole rows, else that layer
+    // leaves fp32 for a dot kernel.
     {
-        int cur = 0, ld = m->z_ld;
+        const int G = m->towers, n_top = m->n_top;
+        FcProblem p{};
+        p.A = act[0]; p.a_f32 = false; p.lda = m->z_ld; p.a_stride = 0;
+        p.M = B; p.relu = true; p.groups = G;
+        for (int k = 0; k < G; ++k) {
+            const Layer &dotl = m->top[(size_t)k * n_top + n_top - 1];
+            p.g.dot_w[k] = static_cast<const float *>(dotl.W);
+            p.g.dot_bias[k] = dotl.bias;
+        }
         bool cur_f32 = false, done = false;
-        const Layer &dotl = m->top.back();
-        for (size_t i = 0; i + 1 < m->top.size(); ++i) {
-            const Layer &l = m->top[i];
-            const int nxt = 1 + (int)(i & 1);
-            const bool feeds_dot = i + 2 == m->top.size();
+        for (int i = 0; i + 1 < n_top; ++i) {
+            const Layer &l = m->top[i];  // shape of layer i in every tower
+            for (int k = 0; k < G; ++k) {
+                p.g.W[k] = m->top[(size_t)k * n_top + i].W;
+                p.g.bias[k] = m->top[(size_t)k * n_top + i].bias;
+            }
+            p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
+            const bool feeds_dot = i + 2 == n_top;
             if (feeds_dot && fc_can_fuse_dot(l.Npad)) {
-                REC_TRY(launch_fc(act[cur], false, ld, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true, nullptr,
-                                  false, 0, static_cast<const float *>(dotl.W), dotl.bias, dev_logits, s));
+                p.C = nullptr; p.out_f32 = false; p.ldc = 0; p.c_stride = 0;
+                p.dot_out = dev_logits; p.dot_ld = G;
+                REC_TRY(launch_fc(p, s));
                 done = true;
                 break;
             }
-            const int ldc = feeds_dot ? l.Npad : m->act_ld;
-            REC_TRY(launch_fc(act[cur], false, ld, B, l.K, l.Kpad, l.W, l.bias, l.Npad, true, act[nxt],
-                              feeds_dot, ldc, nullptr, nullptr, nullptr, s));
-            cur = nxt; ld = ldc; cur_f32 = feeds_dot;
+            p.C = act[1 + (i & 1)]; p.out_f32 = feeds_dot; p.ldc = G * l.Npad; p.c_stride = l.Npad;
+            REC_TRY(launch_fc(p, s));
+            p.A = p.C; p.lda = p.ldc; p.a_stride = p.c_stride; p.a_f32 = false;
+            cur_f32 = feeds_dot;
         }
         if (!done)
-            REC_TRY(launch_rowdot(act[cur], cur_f32, ld, B, dotl.Kpad, static_cast<const float *>(dotl.W),
-                                  dotl.bias, dev_logits, s));
+            REC_TRY(launch_rowdot(p.A, cur_f32, p.lda, p.a_stride, B, m->top[n_top - 1].Kpad, p.g, G,
+                                  dev_logits, G, s));
     }
     REC_MARK();
 #undef REC_MARK
@@ -427,8 +472,12 @@ rec_status rec_debug_get(rec_model *m, int32_t what, const void **dev_ptr, int64
     int64_t ld = 0;
     switch (what) {
     case REC_DBG_OFFSETS: *dev_ptr = m->at<void>(m->off_offsets); ld = 0; break;
-    case REC_DBG_POOLED: *dev_ptr = m->at<void>(m->off_pooled); ld = m->D; break;
-    case REC_DBG_BOTTOM_OUT: *dev_ptr = m->at<void>(m->off_x0); ld = m->d_pad; break;
+    case REC_DBG_POOLED:
+        if (m->interaction != REC_INTERACT_DOT) return REC_ERR_STATE;
+        *dev_ptr = m->at<void>(m->off_pooled); ld = m->D; break;
+    case REC_DBG_BOTTOM_OUT:
+        if (m->bottom.empty()) return REC_ERR_STATE;
+        *dev_ptr = m->at<void>(m->off_x0); ld = m->x0_ld; break;
     case REC_DBG_INTERACT: *dev_ptr = m->at<void>(m->off_act[0]); ld = m->z_ld; break;
     default: return REC_ERR_ARG;
     }

@@ -43,9 +43,18 @@ hipError_t launch_clear_err(ErrRecord *err, hipStream_t s);
 hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *offsets,
                        long long *block_sums, ErrRecord *err, hipStream_t s);
 
-// S1. pooled[b][t][:] = sum of the rows of bag (t, b); fp32 accumulation.
+// Where S1 leaves the sum of bag (t, b): fp32 pooled[b][t][:], or (z != null,
+// concatenation model) narrowed to bf16 at z[b][col0 + t * D ...], row stride ldz.
+struct PoolOut {
+    float *pooled;
+    void *z;
+    int ldz, col0;
+};
+
+// S1. Sum of the rows of every bag, fp32 accumulation.  nnz (the batch's id
+// count) only picks the launch shape: bags of a few ids share a wavefront.
 hipError_t launch_pool(const TableDesc *tables, int dtype, int T, int D, int B,
-                       const int32_t *indices, const int32_t *offsets, float *pooled,
+                       const int32_t *indices, const int32_t *offsets, PoolOut out, long long nnz,
                        ErrRecord *err, hipStream_t s);
 
 // S1 with the tables' hot rows served from an LDS copy (hcap: power of two >= the
@@ -55,23 +64,39 @@ hipError_t launch_pool_hot(const TableDesc *tables, int dtype, int T, int D, int
                            const int32_t *indices, const int32_t *offsets, float *pooled, int hcap,
                            int num_cus, ErrRecord *err, hipStream_t s);
 
-// S2 / S4. C[m][n] = act(sum_k A[m][k] * W[n][k] + bias[n]) on bf16 MFMA.
-//   A: bf16 [M][lda] or (a_f32) fp32 [M][lda] with only k < K valid
-//   W: bf16 [Npad][Kpad], bias fp32 [Npad] (zero padded)
-//   C: bf16 [M][ldc] or (out_f32) fp32 [M][ldc], ldc >= Npad
+// S2 / S4. One layer of `groups` stacks that run side by side (the task towers
+// of the Predict-FC; 1 for a single stack), stack g being
+//   C_g[m][n] = act(sum_k A_g[m][k] * W_g[n][k] + bias_g[n])   on bf16 MFMA, with
+//   A_g = A + g * a_stride: bf16 [M][lda] or (a_f32) fp32 [M][lda] with only k < K
+//         valid; a_stride = 0 when all stacks read the same input
+//   W_g: bf16 [Npad][Kpad], bias_g fp32 [Npad] (zero padded)
+//   C_g = C + g * c_stride: bf16 [M][ldc] or (out_f32) fp32 [M][ldc]
 // With dot_out != null (allowed when fc_can_fuse_dot(Npad)) C is not stored;
-// instead dot_out[m] = sum_n act(C[m][n]) * dot_w[n] + dot_bias[0], the
-// one-output layer that follows, in fp32.
+// instead dot_out[m * dot_ld + g] = sum_n act(C_g[m][n]) * dot_w_g[n] + dot_bias_g[0],
+// the one-output layer that follows, in fp32.
+constexpr int MAX_GROUPS = REC_MAX_TOWERS;
+struct FcGroups {
+    const void *W[MAX_GROUPS];
+    const float *bias[MAX_GROUPS];
+    const float *dot_w[MAX_GROUPS];
+    const float *dot_bias[MAX_GROUPS];
+};
+struct FcProblem {
+    const void *A; bool a_f32; int lda; long long a_stride;
+    int M, K, Kpad, Npad; bool relu;
+    void *C; bool out_f32; int ldc; long long c_stride;
+    int groups;
+    FcGroups g;
+    float *dot_out; int dot_ld;
+};
 bool fc_can_fuse_dot(int Npad);
-hipError_t launch_fc(const void *A, bool a_f32, int lda, int M, int K, int Kpad,
-                     const void *W, const float *bias, int Npad, bool relu, void *C,
-                     bool out_f32, int ldc, const float *dot_w, const float *dot_bias,
-                     float *dot_out, hipStream_t s);
+hipError_t launch_fc(const FcProblem &p, hipStream_t s);
 
-// Last Predict-FC layer: logits[m] = sum_k A[m][k] * w[k] + bias[0], fp32 arithmetic.
-// A is fp32 [M][lda] (a_f32) or bf16 [M][lda]; w is fp32 [Kpad], zero padded.
-hipError_t launch_rowdot(const void *A, bool a_f32, int lda, int M, int Kpad, const float *w,
-                         const float *bias, float *logits, hipStream_t s);
+// Last Predict-FC layer of every stack: logits[m * ld + g] = sum_k A_g[m][k] * w_g[k] + bias_g[0]
+// in fp32.  A_g = A + g * a_stride is fp32 [M][lda] (a_f32) or bf16 [M][lda];
+// w_g = groups.dot_w[g] is fp32 [Kpad], zero padded, bias_g = groups.dot_bias[g].
+hipError_t launch_rowdot(const void *A, bool a_f32, int lda, long long a_stride, int M, int Kpad,
+                         const FcGroups &groups, int n_groups, float *logits, int ld, hipStream_t s);
 hipError_t launch_pack_dot(const float *W, const float *b, int K, int Kpad, float *W_packed,
                            float *bias_packed, hipStream_t s);
 
@@ -83,5 +108,11 @@ hipError_t launch_pack_fc(const float *W, const float *b, int N, int K, int Npad
 size_t interact_lds_bytes_per_sample(int T, int D);
 hipError_t launch_interact(const float *x0, int ldx0, const float *pooled, int B, int T, int D,
                            void *out_bf16, int ldo, hipStream_t s);
+
+
+// Concatenation model: z[b][0 .. w0) = bf16(x0[b][0 .. w0)) and z[b][width .. ldz) = 0;
+// the looked-up vectors in between are written by S1.
+hipError_t launch_concat_dense(const float *x0, int ldx0, int w0, int B, void *z_bf16, int width,
+                               int ldz, hipStream_t s);
 
 }  // namespace rec

@@ -12,13 +12,21 @@ POOL_RTOL = 1e-5      # fp32 pooling vs fp64 oracle
 LOGIT_RTOL = 2e-2     # bf16 MLP logits vs exact oracle
 
 
-def make_model(binding, tables, bottom, top, max_batch, max_nnz, num_dense):
-    """tables: list of numpy [R, D] (f32 or f16); bottom/top: [(W, b)] fp32 numpy."""
+def _as_towers(top):
+    """[(W, b)] -> [[(W, b)]]; a list of towers stays as it is."""
+    return top if isinstance(top[0], list) else [top]
+
+
+def make_model(binding, tables, bottom, top, max_batch, max_nnz, num_dense, interaction="dot"):
+    """tables: list of numpy [R, D] (f32 or f16); bottom: [(W, b)] fp32 numpy (may be
+    empty); top: [(W, b)], or a list of such stacks, one per tower."""
     T, D = len(tables), tables[0].shape[1]
     dt = "f16" if tables[0].dtype == np.float16 else "f32"
+    towers = _as_towers(top)
     bw = [num_dense] + [W.shape[0] for W, _ in bottom]
-    tw = [top[0][0].shape[1]] + [W.shape[0] for W, _ in top]
-    m = binding.RecModel(T, D, [t.shape[0] for t in tables], dt, num_dense, bw, tw, max_batch, max_nnz)
+    tw = [towers[0][0][0].shape[1]] + [W.shape[0] for W, _ in towers[0]]
+    m = binding.RecModel(T, D, [t.shape[0] for t in tables], dt, num_dense, bw, tw, max_batch, max_nnz,
+                         interaction=interaction, towers=len(towers))
     for t, tab in enumerate(tables):
         m.load_table(t, torch.from_numpy(np.ascontiguousarray(tab)).cuda())
     load_mlps(binding, m, bottom, top)
@@ -28,8 +36,9 @@ def make_model(binding, tables, bottom, top, max_batch, max_nnz, num_dense):
 def load_mlps(binding, m, bottom, top):
     for i, (W, b) in enumerate(bottom):
         m.load_mlp(binding.REC_BOTTOM, i, torch.from_numpy(W), torch.from_numpy(b))
-    for i, (W, b) in enumerate(top):
-        m.load_mlp(binding.REC_TOP, i, torch.from_numpy(W), torch.from_numpy(b))
+    for k, tower in enumerate(_as_towers(top)):
+        for i, (W, b) in enumerate(tower):
+            m.load_mlp(binding.REC_TOP + k, i, torch.from_numpy(W), torch.from_numpy(b))
 
 
 def make_workload_model(binding, w: synth.Workload, max_batch=None):
@@ -38,14 +47,17 @@ def make_workload_model(binding, w: synth.Workload, max_batch=None):
     hi = w.pooling[1] if w.pooling[0] == "fixed" else w.pooling[3]
     m = binding.RecModel(w.num_tables, w.emb_dim, [w.rows] * w.num_tables, w.table_dtype,
                          w.num_dense, list(w.bottom), list(w.top), max_batch,
-                         min(max_batch * w.num_tables * hi, 2 ** 31 - 1))
+                         min(max_batch * w.num_tables * hi, 2 ** 31 - 1),
+                         interaction=w.interaction, towers=w.towers)
     tdt = torch.float16 if w.table_dtype == "f16" else torch.float32
     for t in range(w.num_tables):
         tab = torch.empty((w.rows, w.emb_dim), dtype=tdt, device="cuda")
         st = binding.rec_synth_fill_table(tab, w.seed, t)
         assert st == binding.REC_OK
         m.load_table(t, tab)
-    bottom, top = synth.draw_mlp(w, "bottom"), synth.draw_mlp(w, "top")
+    bottom = synth.draw_mlp(w, "bottom")
+    top = synth.draw_mlp(w, "top") if w.towers == 1 and w.interaction == "dot" else \
+        [synth.draw_mlp(w, "top", k) for k in range(w.towers)]
     load_mlps(binding, m, bottom, top)
     torch.cuda.synchronize()
     return m, bottom, top
@@ -87,6 +99,10 @@ def check_logits(got: np.ndarray, exact: np.ndarray, mirror: np.ndarray = None):
     got = got.astype(np.float64)
     if exact.size == 0:
         return
+    if exact.ndim == 2:     # one column per tower, each held to the bar on its own
+        for k in range(exact.shape[1]):
+            check_logits(got[:, k], exact[:, k], None if mirror is None else mirror[:, k])
+        return
     assert np.linalg.norm(got - exact) <= LOGIT_RTOL * np.linalg.norm(exact) + 1e-12, \
         float(np.linalg.norm(got - exact) / np.linalg.norm(exact))
     assert np.abs(got - exact).max() <= LOGIT_RTOL * np.abs(exact).max() + 1e-12, \
@@ -103,7 +119,10 @@ def oracle_on_slice(w: synth.Workload, batch: synth.Batch, samples, bottom, top,
     materialising only the rows those samples touch."""
     sub = synth.slice_samples(w, batch, np.asarray(samples))
     tabs, cidx = synth.compact_tables(w, sub, len(samples))
-    out = orc.forward(sub.dense, tabs, cidx, sub.lengths, bottom, top, mode)
+    if w.interaction == "concat":
+        out = orc.forward_towers(sub.dense, tabs, cidx, sub.lengths, bottom, _as_towers(top), mode)
+    else:
+        out = orc.forward(sub.dense, tabs, cidx, sub.lengths, bottom, top, mode)
     P, A, nbad, _ = orc.pool(tabs, cidx, sub.lengths, len(samples), want_abs=True)
     assert nbad == 0
     out["abs_sum"] = A

@@ -72,6 +72,30 @@ def test_create_validates_shapes(binding):
     b.rec_destroy(h)
 
 
+def test_concat_and_tower_shapes(binding):
+    ok = dict(num_tables=2, emb_dim=8, rows=[10, 10], table_dtype=binding.REC_F32, num_dense=4,
+              max_batch=4, max_nnz=100)
+    # concat: first Predict-FC width must be w0 + T * D
+    st, h = binding.rec_create(bottom_widths=[4], top_widths=[4 + 16, 8, 1],
+                               interaction=binding.REC_INTERACT_CONCAT, num_towers=2, **ok)
+    assert st == binding.REC_OK
+    assert binding.rec_mlp_packed_bytes(h, binding.REC_TOP + 1, 0) > 0
+    assert binding.rec_mlp_packed_bytes(h, binding.REC_TOP + 2, 0) == 0      # no such tower
+    assert binding.rec_mlp_packed_bytes(h, binding.REC_BOTTOM, 0) == 0       # no Bottom-FC
+    binding.rec_destroy(h)
+    st, _ = binding.rec_create(bottom_widths=[4], top_widths=[8 + 3, 8, 1],
+                               interaction=binding.REC_INTERACT_CONCAT, num_towers=1, **ok)
+    assert st == binding.REC_ERR_SHAPE
+    st, _ = binding.rec_create(bottom_widths=[4], top_widths=[20, 1], interaction=2, num_towers=1, **ok)
+    assert st == binding.REC_ERR_ARG
+    st, _ = binding.rec_create(bottom_widths=[4], top_widths=[20, 1], interaction=binding.REC_INTERACT_CONCAT,
+                               num_towers=binding.REC_MAX_TOWERS + 1, **ok)
+    assert st == binding.REC_ERR_ARG
+    # pairwise dots without a Bottom-FC need num_dense = emb_dim
+    st, _ = binding.rec_create(bottom_widths=[4], top_widths=[8 + 3, 1], **ok)
+    assert st == binding.REC_ERR_SHAPE
+
+
 def test_null_and_order_errors_without_device(binding):
     b = binding
     lib = C.CDLL(b.LIB_PATH)
