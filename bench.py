@@ -4,6 +4,10 @@
 One step = one rec_forward() over one synthetic batch: offsets scan, embedding
 bag pooling, Bottom-FC, pairwise-dot interaction, Predict-FC.  Inputs and
 tables are resident in HBM before the timed region.  Prints ONE JSON line.
+The default workload (rmc2) is bound by the pooling kernel and its roofline is
+HBM bandwidth; --workload mtwnd (one lookup per table, concatenation, four
+Predict-FC towers) is bound by its first tower layer and reports that GEMM
+against the bf16 MFMA peak.
 
 The timed region runs one model instance on one stream.  --instances N
 co-locates N instances (own stream and workspace each, tables shared) which
@@ -26,6 +30,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 
 # HBM traffic of one pooling launch from rocprofv3 counter runs (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy: 2.000 and
@@ -74,7 +79,10 @@ def cpu_baseline(w, batch, bottom, top, n_samples: int) -> dict:
     cores = len(os.sched_getaffinity(0))
     threads = orc.set_threads(cores)
     t0 = time.perf_counter()
-    orc.forward(sub.dense, tabs, cidx, sub.lengths, bottom, top)
+    if w.interaction == "concat":
+        orc.forward_towers(sub.dense, tabs, cidx, sub.lengths, bottom, top)
+    else:
+        orc.forward(sub.dense, tabs, cidx, sub.lengths, bottom, top)
     dt = time.perf_counter() - t0
     return {"value": n_samples / dt, "unit": "samples/s", "cores": threads, "kind": "oracle",
             "sample": f"first {n_samples} samples of batch 0 of {w.name} (rows they touch "
@@ -88,7 +96,8 @@ def build_model(binding, synth, torch, w, max_batch, share_tables=None):
     hi = w.pooling[1] if w.pooling[0] == "fixed" else w.pooling[3]
     m = binding.RecModel(w.num_tables, w.emb_dim, [w.rows] * w.num_tables, w.table_dtype,
                          w.num_dense, list(w.bottom), list(w.top), max_batch,
-                         min(max_batch * w.num_tables * hi, 2 ** 31 - 1))
+                         min(max_batch * w.num_tables * hi, 2 ** 31 - 1),
+                         interaction=w.interaction, towers=w.towers)
     tdt = torch.float16 if w.table_dtype == "f16" else torch.float32
     for t in range(w.num_tables):
         if share_tables is not None:
@@ -97,13 +106,21 @@ def build_model(binding, synth, torch, w, max_batch, share_tables=None):
             tab = torch.empty((w.rows, w.emb_dim), dtype=tdt, device=dev)
             assert binding.rec_synth_fill_table(tab, w.seed, t) == binding.REC_OK
         m.load_table(t, tab)
-    bottom, top = synth.draw_mlp(w, "bottom"), synth.draw_mlp(w, "top")
+    bottom = synth.draw_mlp(w, "bottom")
+    towers = [synth.draw_mlp(w, "top", k) for k in range(w.towers)]
     for i, (W, b) in enumerate(bottom):
         m.load_mlp(binding.REC_BOTTOM, i, torch.from_numpy(W), torch.from_numpy(b))
-    for i, (W, b) in enumerate(top):
-        m.load_mlp(binding.REC_TOP, i, torch.from_numpy(W), torch.from_numpy(b))
+    for k, tower in enumerate(towers):
+        for i, (W, b) in enumerate(tower):
+            m.load_mlp(binding.REC_TOP + k, i, torch.from_numpy(W), torch.from_numpy(b))
     torch.cuda.synchronize()
-    return m, bottom, top
+    # the oracle's pairwise-dot forward takes one stack, its tower forward a list of them
+    return m, bottom, (towers if w.interaction == "concat" else towers[0])
+
+
+def new_logits(torch, w, batch, dev):
+    shape = (batch,) if w.towers == 1 else (batch, w.towers)
+    return torch.empty(shape, dtype=torch.float32, device=dev)
 
 
 def pick_concurrent_streams(torch, dev, n):
@@ -163,7 +180,7 @@ def latency_sweep(args) -> int:
         hb = [synth.draw_batch(w, 1000 + i, cdf) for i in range(2)]
         db = [(torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
                torch.from_numpy(b.lengths).to(dev)) for b in hb]
-        logits = torch.empty(B, dtype=torch.float32, device=dev)
+        logits = new_logits(torch, w, B, dev)
         for i in range(args.warmup):
             m.forward(*db[i % 2], logits)
         torch.cuda.synchronize()
@@ -358,7 +375,7 @@ def main() -> int:
         return hb, db
 
     host_batches, dev_batches = make_batches(w, args.batches, 0)
-    logits = [torch.empty(w.batch, dtype=torch.float32, device=dev) for _ in range(n_inst)]
+    logits = [new_logits(torch, w, w.batch, dev) for _ in range(n_inst)]
     torch.cuda.synchronize()
     log(f"{args.batches} batches of {w.batch} resident, nnz[0] = {host_batches[0].nnz} "
         f"({time.time() - t0:.1f} s)")
@@ -373,7 +390,7 @@ def main() -> int:
         # One replay = one forward over each distinct batch, single instance.
         assert n_inst == 1
         per = len(dev_batches)
-        glog = [torch.empty(w.batch, dtype=torch.float32, device=dev) for _ in range(per)]
+        glog = [new_logits(torch, w, w.batch, dev) for _ in range(per)]
         with torch.cuda.stream(streams[0]):
             cap = binding.CapturedForward(m, dev_batches, glog)
         args.steps = max(per, args.steps // per * per)
@@ -426,11 +443,22 @@ def main() -> int:
         model.set_profiling(0)
         pool_bytes = float(np.mean([algorithmic_pool_bytes(wl, b) for b in batches_used]))
         achieved = pool_bytes / (avg["pool"] * 1e-3) / 1e9
-        return avg, {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm",
-                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_pool_traffic(wl),
-                     "bytes_per_launch": pool_bytes, "avg_launch_ms": avg["pool"],
-                     "launches_timed": count}
+        pool = {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm",
+                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_pool_traffic(wl),
+                "bytes_per_launch": pool_bytes, "avg_launch_ms": avg["pool"],
+                "launches_timed": count}
+        if wl.interaction != "concat":
+            return avg, pool
+        # Dense-dominated shape: the first Predict-FC layer of all towers is one
+        # launch and the longest kernel; its algorithmic work is 2 * B * K * N per tower.
+        flops = 2.0 * wl.batch * wl.top[0] * wl.top[1] * wl.towers
+        tf = flops / (avg["top_first"] * 1e-3) / 1e12
+        return avg, {"kernel": "fc_kernel (first Predict-FC layer of all towers, one launch)",
+                     "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "flops_per_launch": flops, "avg_launch_ms": avg["top_first"],
+                     "launches_timed": count, "pooling": pool}
 
     stage_avg = roofline = None
     if use_events:
@@ -456,7 +484,7 @@ def main() -> int:
             st_solo, rf_solo = solo(dev_batches, host_batches, w)
             extra["roofline_single_instance"] = rf_solo
             extra["stage_ms_single_instance"] = st_solo
-        if w.index_dist[0] == "zipf":
+        if w.index_dist[0] == "zipf" and w.interaction == "dot":
             wu = w.with_uniform_indices()
             hbu, dbu = make_batches(wu, 2, 500)
             st_u, rf_u = solo(dbu, hbu, wu)
@@ -471,7 +499,7 @@ def main() -> int:
         cm = [m] + [build_model(binding, synth, torch, w, w.batch, share_tables=m)[0]
                     for _ in range(nc - 1)]
         cs = pick_concurrent_streams(torch, dev, nc)
-        cl = [torch.empty(w.batch, dtype=torch.float32, device=dev) for _ in range(nc)]
+        cl = [new_logits(torch, w, w.batch, dev) for _ in range(nc)]
 
         def cstep(i):
             with torch.cuda.stream(cs[i % nc]):
@@ -495,7 +523,8 @@ def main() -> int:
         cpu = cpu_baseline(w, host_batches[0], bottom, top, args.cpu_samples)
 
     out = {
-        "metric": "samples/sec per GPU + embedding-bag HBM GB/s (% of peak), RMC2-style",
+        "metric": ("samples/sec per GPU + embedding-bag HBM GB/s (% of peak), RMC2-style" if w.interaction == "dot"
+                   else "samples/sec per GPU + first Predict-FC layer TFLOP/s (% of bf16 MFMA peak), MT-WnD-style"),
         "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
@@ -503,7 +532,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.num_tables} tables x {w.rows} rows x dim {w.emb_dim} "
                                f"{w.table_dtype}, pooling {w.pooling}, ids {w.index_dist}, "
-                               f"bottom {list(w.bottom)}, top {list(w.top)}",
+                               f"bottom {list(w.bottom)}, top {list(w.top)}"
+                               + (f" x {w.towers} towers, concatenation" if w.interaction == "concat" else ""),
                    "batch": w.batch, "distinct_batches": args.batches,
                    "co_located_instances": n_inst, "hip_graph": bool(args.graph), "hot_rows_per_table": args.hot_rows,
                    "mean_nnz": float(np.mean([b.nnz for b in host_batches]))},

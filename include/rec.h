@@ -86,10 +86,11 @@ enum {
                               the Predict-FC input of either model shape          */
 };
 
-/* Stages timed by rec_set_profiling(). */
+/* Stages timed by rec_set_profiling().  The Predict-FC is split into its first
+ * layer (one launch, the widest matrix product of the model) and the rest. */
 enum {
     REC_STAGE_SCAN = 0, REC_STAGE_POOL = 1, REC_STAGE_BOTTOM = 2,
-    REC_STAGE_INTERACT = 3, REC_STAGE_TOP = 4, REC_NUM_STAGES = 5
+    REC_STAGE_INTERACT = 3, REC_STAGE_TOP_FIRST = 4, REC_STAGE_TOP_REST = 5, REC_NUM_STAGES = 6
 };
 
 /*

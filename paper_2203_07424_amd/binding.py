@@ -31,8 +31,8 @@ REC_INTERACT_DOT, REC_INTERACT_CONCAT = 0, 1
 REC_MAX_TOWERS = 8
 REC_DBG_OFFSETS, REC_DBG_POOLED, REC_DBG_BOTTOM_OUT, REC_DBG_INTERACT = 0, 1, 2, 3
 REC_OPT_OVERLAP_DENSE = 0
-REC_NUM_STAGES = 5
-STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top")
+REC_NUM_STAGES = 6
+STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top_first", "top_rest")
 
 EXPORTS = ("rec_create", "rec_destroy", "rec_workspace_bytes", "rec_bind_workspace",
            "rec_load_tables", "rec_load_hot_rows", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_check",

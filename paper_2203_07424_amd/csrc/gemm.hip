@@ -344,7 +344,7 @@ __global__ __launch_bounds__(256) void pack_fc_kernel(const float *__restrict__ 
 
 }  // namespace
 
-bool fc_can_fuse_dot(int Npad) { return Npad == 64 || Npad == 128; }
+bool fc_can_fuse_dot(int Npad) { return Npad == 64 || Npad == 128 || Npad == 256; }
 
 hipError_t launch_fc(const FcProblem &a, hipStream_t s)
 {
@@ -354,10 +354,12 @@ hipError_t launch_fc(const FcProblem &a, hipStream_t s)
         return hipErrorInvalidValue;
     if (a.dot_out) {
         // The block must own whole rows.
+        if (Npad == 256) return launch_tile<64, 256, 1, 2>(a, s);
         if (Npad == 128) return launch_tile<32, 128, 1, 4>(a, s);
         if (Npad == 64) return launch_tile<64, 64, 2, 4>(a, s);
         return hipErrorInvalidValue;
     }
+    if (a.num_cus > 0 && fc_big_applies(a, a.num_cus)) return launch_fc_big(a, a.num_cus, s);
     // Large tiles only where they still give every compute unit a block.
     const long long big_blocks = (long long)a.groups * (Npad / 128) * ((M + 127) / 128);
     if (Npad % 128 == 0 && big_blocks >= 256) return launch_tile<128, 128, 2, 2>(a, s);

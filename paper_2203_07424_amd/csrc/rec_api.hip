@@ -337,7 +337,7 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         // ReLU after every layer; the last one leaves fp32 for the interaction.
         FcProblem p{};
         p.A = dev_dense; p.a_f32 = true; p.lda = m->F;
-        p.M = B; p.relu = true; p.groups = 1;
+        p.M = B; p.relu = true; p.groups = 1; p.num_cus = m->num_cus;
         for (size_t i = 0; i < m->bottom.size(); ++i) {
             const Layer &l = m->bottom[i];
             const bool last = i + 1 == m->bottom.size();
@@ -406,14 +406,14 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         const int G = m->towers, n_top = m->n_top;
         FcProblem p{};
         p.A = act[0]; p.a_f32 = false; p.lda = m->z_ld; p.a_stride = 0;
-        p.M = B; p.relu = true; p.groups = G;
+        p.M = B; p.relu = true; p.groups = G; p.num_cus = m->num_cus;
         for (int k = 0; k < G; ++k) {
             const Layer &dotl = m->top[(size_t)k * n_top + n_top - 1];
             p.g.dot_w[k] = static_cast<const float *>(dotl.W);
             p.g.dot_bias[k] = dotl.bias;
         }
-        bool cur_f32 = false, done = false;
-        for (int i = 0; i + 1 < n_top; ++i) {
+        bool cur_f32 = false, done = false, first_marked = false;
+        for (int i = 0; i + 1 < n_top && !done; ++i) {
             const Layer &l = m->top[i];  // shape of layer i in every tower
             for (int k = 0; k < G; ++k) {
                 p.g.W[k] = m->top[(size_t)k * n_top + i].W;
@@ -426,16 +426,21 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
                 p.dot_out = dev_logits; p.dot_ld = G;
                 REC_TRY(launch_fc(p, s));
                 done = true;
-                break;
+            } else {
+                p.C = act[1 + (i & 1)]; p.out_f32 = feeds_dot; p.ldc = G * l.Npad; p.c_stride = l.Npad;
+                REC_TRY(launch_fc(p, s));
+                p.A = p.C; p.lda = p.ldc; p.a_stride = p.c_stride; p.a_f32 = false;
+                cur_f32 = feeds_dot;
             }
-            p.C = act[1 + (i & 1)]; p.out_f32 = feeds_dot; p.ldc = G * l.Npad; p.c_stride = l.Npad;
-            REC_TRY(launch_fc(p, s));
-            p.A = p.C; p.lda = p.ldc; p.a_stride = p.c_stride; p.a_f32 = false;
-            cur_f32 = feeds_dot;
+            if (i == 0) {  // the first (widest) layer is timed on its own
+                REC_MARK();
+                first_marked = true;
+            }
         }
         if (!done)
             REC_TRY(launch_rowdot(p.A, cur_f32, p.lda, p.a_stride, B, m->top[n_top - 1].Kpad, p.g, G,
                                   dev_logits, G, s));
+        if (!first_marked) REC_MARK();
     }
     REC_MARK();
 #undef REC_MARK

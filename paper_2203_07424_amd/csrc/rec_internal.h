@@ -88,9 +88,16 @@ struct FcProblem {
     int groups;
     FcGroups g;
     float *dot_out; int dot_ld;
+    int num_cus;  // compute units of the device; 0 = unknown (never picks the wide-tile kernels)
 };
 bool fc_can_fuse_dot(int Npad);
 hipError_t launch_fc(const FcProblem &p, hipStream_t s);
+
+// The same product with 256-row block tiles (bf16 input, C stored), for layers
+// wide and batches large enough that such tiles still cover the chip;
+// launch_fc() takes this path by itself when fc_big_applies().
+bool fc_big_applies(const FcProblem &p, int num_cus);
+hipError_t launch_fc_big(const FcProblem &p, int num_cus, hipStream_t s);
 
 // Last Predict-FC layer of every stack: logits[m * ld + g] = sum_k A_g[m][k] * w_g[k] + bias_g[0]
 // in fp32.  A_g = A + g * a_stride is fp32 [M][lda] (a_f32) or bf16 [M][lda];

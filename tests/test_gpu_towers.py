@@ -54,7 +54,8 @@ CASES = [
     (6, 250, 64, np.float16, 40, 16, (), (130, 70), 2, (0, 60)),      # long bags: one wave per bag
     (2, 100, 8, np.float32, 257, 5, (), (), 5, (1, 1)),               # towers of one (one-output) layer
     (3, 100, 256, np.float32, 19, 8, (16,), (32,), 1, (1, 2)),        # 1 KB rows, one tower
-    (3, 100, 32, np.float16, 90, 8, (), (40, 200), 3, (1, 1)),        # last hidden layer too wide to fuse the dot
+    (3, 100, 32, np.float16, 90, 8, (), (40, 300), 3, (1, 1)),        # last hidden layer too wide to fuse the dot
+    (3, 100, 32, np.float16, 300, 8, (), (40, 200), 2, (1, 1)),       # dot fused into a 256-wide last hidden layer
 ]
 
 
@@ -209,4 +210,25 @@ def test_full_size_tower_workload_sampled_against_oracle(binding):
     # properties that hold for every sample: finite, and towers differ
     assert np.isfinite(logits).all() and logits.shape == (w.batch, w.towers)
     assert np.abs(logits[:, 0] - logits[:, 1]).max() > 0
+    m.close()
+
+
+@pytest.mark.parametrize("hidden,towers,B", [((1280, 64), 8, 1100), ((640, 200), 8, 1100), ((1024, 512), 2, 2048)])
+def test_wide_tower_layers_on_ragged_batches(binding, hidden, towers, B):
+    # Layers wide enough, on batches large enough, for the 256-row block tiles
+    # (256 x 256 and 256 x 128), with a batch that is not a multiple of the tile.
+    say("wide towers", hidden, towers, B)
+    g = np.random.default_rng(91)
+    T, R, D, F = 6, 300, 32, 8
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(np.float16) for _ in range(T)]
+    lens = np.ones(T * B, dtype=np.int32)
+    idx = g.integers(0, R, T * B).astype(np.int32)
+    bottom, tw = stacks(g, F, (), T, D, hidden, towers)
+    dense = g.standard_normal((B, F)).astype(np.float32)
+    m = H.make_model(binding, tabs, bottom, tw, B, idx.size, F, interaction="concat")
+    logits = H.run(m, synth.Batch(dense, idx, lens))
+    assert m.check() == (binding.REC_OK, -1)
+    exact = orc.forward_towers(dense, tabs, idx, lens, bottom, tw, orc.EXACT)
+    mirror = orc.forward_towers(dense, tabs, idx, lens, bottom, tw, orc.BF16_MIRROR)
+    H.check_logits(logits, exact["logits"], mirror["logits"])
     m.close()
