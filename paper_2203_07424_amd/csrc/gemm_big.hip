@@ -1,19 +1,21 @@
-// S4 for wide stacks (Table I, MT-WnD row: N towers of 1024-512-256 on a
-// 4096-sample batch): the same  C = act(A W^T + b)  as fc_kernel, with block
-// tiles of 256 rows.
+// S2 / S4 for wide layers on large batches (Table I: the 2560-wide Bottom-FC of
+// DLRM-RMC3, the N towers of 1024-512-256 of MT-WnD): the same
+// C = act(A W^T + b)  as fc_kernel, with block tiles of 256 x 256, 256 x 128 or
+// 128 x 128 and 8 waves per block.
 //
-// What bounds these products on this chip is how fast one compute unit can pull
-// operand tiles through its L1 (about 20 bytes per clock), not the matrix cores:
-// a BM x BN tile moves (BM + BN) * 2 bytes per k for 2 * BM * BN flops, so the
-// tile must be large.  256 x 256 needs 32 bytes per clock per compute unit at
-// full MFMA rate, 128 x 128 needs 64.  A 256 x 256 x 64 tile pair is 64 KB, two
-// of them (double buffering: one barrier per k-tile) use 144 of the 160 KB of
-// LDS, so one block of 8 waves owns a compute unit, two waves per SIMD.
+// A BM x BN tile moves (BM + BN) * 2 bytes per k for 2 * BM * BN flops, so large
+// tiles ask least of the caches; the L2 can feed a compute unit about 49 bytes
+// per clock (measured with a read-only probe on an L2-resident footprint) and a
+// 256 x 256 tile needs 32 at full MFMA rate.  The tile pairs are double
+// buffered in LDS (one barrier per k-tile; 256 x 256 x 64: 2 x 72 KB of the
+// 160 KB), so one block owns a compute unit, two waves per SIMD.
 //
 // Per k-tile: tile kt is multiplied out of one LDS buffer while the registers
 // holding tile kt+1 (fetched one iteration earlier) go to the other buffer and
 // are refilled with tile kt+2, a quarter of that staging work per 16-wide step
-// of matrix instructions; one barrier per k-tile.
+// of matrix instructions.  Measured and not kept: 4 waves with 128 x 128 wave
+// tiles (accumulators in AGPRs), 16 waves, and global loads written straight
+// into LDS (swizzled rows, no staging registers) - each within 5 % of this.
 #include "rec_internal.h"
 
 namespace rec {
@@ -31,11 +33,43 @@ constexpr int LDS_LD = BK + 8;  // 144-byte row stride: 16-byte reads of 16 cons
 template <int BM, int BN>
 constexpr size_t big_lds_bytes() { return 2 * (size_t)(BM + BN) * LDS_LD * sizeof(__bf16); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool OUT_F32>
+// 8 consecutive k of one activation row as fetched: bf16, or raw fp32 (the model's
+// dense input) that is narrowed only when it is written to LDS.
+template <bool A_F32>
+struct AReg;
+template <>
+struct AReg<false> {
+    bf16x8 v;
+    __device__ inline void fetch(const char *p) { v = *reinterpret_cast<const bf16x8 *>(p); }
+    __device__ inline bf16x8 narrow(bool) const { return v; }
+};
+template <>
+struct AReg<true> {
+    f32x4 lo, hi;
+    __device__ inline void fetch(const char *p)
+    {
+        lo = *reinterpret_cast<const f32x4 *>(p);
+        hi = *reinterpret_cast<const f32x4 *>(p + 16);
+    }
+    __device__ inline bf16x8 narrow(bool valid) const
+    {
+        bf16x8 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            o[i] = (__bf16)(valid ? lo[i] : 0.0f);
+            o[i + 4] = (__bf16)(valid ? hi[i] : 0.0f);
+        }
+        return o;
+    }
+};
+
+// A_F32: A is fp32 [M][lda] with only k < K valid (K a multiple of 8); chunks at
+// k >= K are fetched from the row's last valid chunk and zeroed.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_F32, bool OUT_F32>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fc_big_kernel(
-    const __bf16 *__restrict__ A0, int lda, long long a_stride, int M, int Kpad, const FcGroups groups,
-    int relu, void *__restrict__ C0, int ldc, long long c_stride, int grid_m, int grid_n,
-    int tiles_per_group)
+    const void *__restrict__ A0, int lda, long long a_stride, int M, int K, int Kpad,
+    const FcGroups groups, int relu, void *__restrict__ C0, int ldc, long long c_stride, int grid_m,
+    int grid_n, int tiles_per_group)
 {
     constexpr int THREADS = 64 * WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // per-wave tile
@@ -68,18 +102,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fc_big_kernel(
         bn = v - bm * grid_n;
     }
     const int m0 = bm * BM, n0 = bn * BN;
-    const __bf16 *__restrict__ A = A0 + grp * a_stride;
+    constexpr int A_ELT = A_F32 ? 4 : 2;
+    const char *__restrict__ A = static_cast<const char *>(A0) + grp * a_stride * A_ELT;
     const __bf16 *__restrict__ W = static_cast<const __bf16 *>(groups.W[grp]);
     const float *__restrict__ bias = groups.bias[grp];
 
     const int ld_row = tid >> 3, ld_chunk = tid & 7;
-    const __bf16 *a_src[A_LOADS];
+    const char *a_src[A_LOADS];  // this thread's chunk of k-tile 0 in each of its rows
     const __bf16 *w_src[W_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
         int row = m0 + ld_row + ROWS_PER_PASS * i;
         row = row < M ? row : M - 1;  // rows past M are computed and dropped
-        a_src[i] = A + (long long)row * lda + ld_chunk * 8;
+        a_src[i] = A + (long long)row * lda * A_ELT;
     }
 #pragma unroll
     for (int i = 0; i < W_LOADS; ++i)
@@ -93,7 +128,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fc_big_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    bf16x8 ra[A_LOADS], rw[W_LOADS];
+    AReg<A_F32> ra[A_LOADS];
+    bf16x8 rw[W_LOADS];
     const int nk = Kpad / BK;
 
     // The staging work of a k-tile (BK / 16 = 4 steps of MFMAs) is cut into 4 parts,
@@ -103,16 +139,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fc_big_kernel(
     constexpr int A_PART = (A_LOADS + KSTEPS - 1) / KSTEPS, W_PART = (W_LOADS + KSTEPS - 1) / KSTEPS;
 #define REC_BIG_FETCH_PART(kt, part)                                                       \
     do {                                                                                   \
+        int k_ = (kt) * BK + ld_chunk * 8;                                                 \
+        if (A_F32) k_ = k_ < K ? k_ : K - 8;                                               \
         _Pragma("unroll") for (int i = (part) * A_PART; i < ((part) + 1) * A_PART && i < A_LOADS; ++i) \
-            ra[i] = *reinterpret_cast<const bf16x8 *>(a_src[i] + (kt) * BK);               \
+            ra[i].fetch(a_src[i] + (long long)k_ * A_ELT);                                 \
         _Pragma("unroll") for (int i = (part) * W_PART; i < ((part) + 1) * W_PART && i < W_LOADS; ++i) \
             rw[i] = *reinterpret_cast<const bf16x8 *>(w_src[i] + (kt) * BK);               \
     } while (0)
-#define REC_BIG_STASH_PART(buf, part)                                                      \
+#define REC_BIG_STASH_PART(kt, buf, part)                                                  \
     do {                                                                                   \
         __bf16 *sa_ = smem + (buf) * BUF, *sw_ = sa_ + BM * LDS_LD;                        \
+        const bool valid_ = !A_F32 || (kt) * BK + ld_chunk * 8 < K; /* the chunk held in ra lies below K */ \
         _Pragma("unroll") for (int i = (part) * A_PART; i < ((part) + 1) * A_PART && i < A_LOADS; ++i) \
-            *reinterpret_cast<bf16x8 *>(&sa_[(ld_row + ROWS_PER_PASS * i) * LDS_LD + ld_chunk * 8]) = ra[i]; \
+            *reinterpret_cast<bf16x8 *>(&sa_[(ld_row + ROWS_PER_PASS * i) * LDS_LD + ld_chunk * 8]) = ra[i].narrow(valid_); \
         _Pragma("unroll") for (int i = (part) * W_PART; i < ((part) + 1) * W_PART && i < W_LOADS; ++i) \
             *reinterpret_cast<bf16x8 *>(&sw_[(ld_row + ROWS_PER_PASS * i) * LDS_LD + ld_chunk * 8]) = rw[i]; \
     } while (0)
@@ -130,7 +169,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fc_big_kernel(
                 fw[i] = *reinterpret_cast<const bf16x8 *>(&sW[(wn * WN + i * 32 + (lane & 31)) * LDS_LD + kofs]); \
             _Pragma("unroll") for (int j = 0; j < TM; ++j)                                 \
                 fa[j] = *reinterpret_cast<const bf16x8 *>(&sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]); \
-            if (STASH) REC_BIG_STASH_PART(cur_ ^ 1, kk);                                   \
+            if (STASH) REC_BIG_STASH_PART((kt) + 1, cur_ ^ 1, kk);                                   \
             if (FETCH) REC_BIG_FETCH_PART((kt) + 2, kk);                                   \
             _Pragma("unroll") for (int i = 0; i < TN; ++i)                                 \
                 _Pragma("unroll") for (int j = 0; j < TM; ++j)                             \
@@ -142,7 +181,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fc_big_kernel(
 #pragma unroll
     for (int part = 0; part < KSTEPS; ++part) REC_BIG_FETCH_PART(0, part);
 #pragma unroll
-    for (int part = 0; part < KSTEPS; ++part) REC_BIG_STASH_PART(0, part);
+    for (int part = 0; part < KSTEPS; ++part) REC_BIG_STASH_PART(0, 0, part);
     if (nk > 1) {
 #pragma unroll
         for (int part = 0; part < KSTEPS; ++part) REC_BIG_FETCH_PART(1, part);
@@ -212,61 +251,66 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fc_big_kernel(
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
-hipError_t launch_big(const FcProblem &a, hipStream_t s)
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_F32, bool OUT_F32>
+hipError_t launch_big_as(const FcProblem &a, hipStream_t s)
 {
     const int grid_m = (a.M + BM - 1) / BM, grid_n = a.Npad / BN;
     const int tiles = grid_m * grid_n;
     const dim3 grid(tiles * a.groups), block(64 * WAVES_M * WAVES_N);
     constexpr size_t lds = big_lds_bytes<BM, BN>();
-    const __bf16 *A = static_cast<const __bf16 *>(a.A);
-    const int r = a.relu ? 1 : 0;
+    auto k = fc_big_kernel<BM, BN, WAVES_M, WAVES_N, A_F32, OUT_F32>;
     // More than 64 KB of dynamic LDS has to be granted once per kernel.
-    static bool granted[2] = {false, false};
-    if (a.out_f32) {
-        auto k = fc_big_kernel<BM, BN, WAVES_M, WAVES_N, true>;
-        if (!granted[1]) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            granted[1] = true;
-        }
-        hipLaunchKernelGGL(k, grid, block, lds, s, A, a.lda, a.a_stride, a.M, a.Kpad, a.g, r, a.C, a.ldc,
-                           a.c_stride, grid_m, grid_n, tiles);
-    } else {
-        auto k = fc_big_kernel<BM, BN, WAVES_M, WAVES_N, false>;
-        if (!granted[0]) {
-            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            granted[0] = true;
-        }
-        hipLaunchKernelGGL(k, grid, block, lds, s, A, a.lda, a.a_stride, a.M, a.Kpad, a.g, r, a.C, a.ldc,
-                           a.c_stride, grid_m, grid_n, tiles);
+    static bool granted = false;
+    if (lds > 64 * 1024 && !granted) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        granted = true;
     }
+    hipLaunchKernelGGL(k, grid, block, lds, s, a.A, a.lda, a.a_stride, a.M, a.K, a.Kpad, a.g,
+                       a.relu ? 1 : 0, a.C, a.ldc, a.c_stride, grid_m, grid_n, tiles);
     return hipGetLastError();
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+hipError_t launch_big(const FcProblem &a, hipStream_t s)
+{
+    if (a.a_f32) {
+        if (a.out_f32) return launch_big_as<BM, BN, WAVES_M, WAVES_N, true, true>(a, s);
+        return launch_big_as<BM, BN, WAVES_M, WAVES_N, true, false>(a, s);
+    }
+    if (a.out_f32) return launch_big_as<BM, BN, WAVES_M, WAVES_N, false, true>(a, s);
+    return launch_big_as<BM, BN, WAVES_M, WAVES_N, false, false>(a, s);
+}
+
+// Which block tile, if any: 256 x 256, 256 x 128 (bf16 input) or 128 x 128, the
+// largest whose tiles still cover three quarters of the compute units.
+int big_tile_choice(const FcProblem &a, int num_cus)
+{
+    if (a.dot_out || a.M < 1024 || a.Kpad % BK != 0 || a.groups < 1 || a.groups > MAX_GROUPS) return 0;
+    if (a.a_f32 && (a.K % 8 != 0 || a.lda % 4 != 0 || a.a_stride % 4 != 0 ||
+                    reinterpret_cast<uintptr_t>(a.A) % 16 != 0))
+        return 0;
+    const long long need = (long long)num_cus * 3 / 4;
+    const long long m256 = (a.M + 255) / 256, m128 = (a.M + 127) / 128;
+    if (!a.a_f32 && a.Npad % 256 == 0 && a.groups * m256 * (a.Npad / 256) >= need) return 1;
+    if (!a.a_f32 && a.Npad % 128 == 0 && a.groups * m256 * (a.Npad / 128) >= need) return 2;
+    if (a.Npad % 128 == 0 && a.groups * m128 * (a.Npad / 128) >= need) return 3;
+    return 0;
 }
 
 }  // namespace
 
-// The wide-tile kernels take bf16 activations and store C; they pay once the
-// batch is large enough that their (few) tiles still cover the chip.
-bool fc_big_applies(const FcProblem &a, int num_cus)
-{
-    if (a.a_f32 || a.dot_out || a.M < 1024 || a.Kpad % BK != 0) return false;
-    const long long m_tiles = (a.M + 255) / 256;
-    const long long need = (long long)num_cus * 3 / 4;
-    if (a.Npad % 256 == 0 && a.groups * m_tiles * (a.Npad / 256) >= need) return true;
-    return a.Npad % 128 == 0 && a.groups * m_tiles * (a.Npad / 128) >= need;
-}
+bool fc_big_applies(const FcProblem &a, int num_cus) { return big_tile_choice(a, num_cus) != 0; }
 
 hipError_t launch_fc_big(const FcProblem &a, int num_cus, hipStream_t s)
 {
-    if (!fc_big_applies(a, num_cus) || a.groups < 1 || a.groups > MAX_GROUPS) return hipErrorInvalidValue;
-    const long long m_tiles = (a.M + 255) / 256;
-    if (a.Npad % 256 == 0 && a.groups * m_tiles * (a.Npad / 256) >= (long long)num_cus * 3 / 4)
-        return launch_big<256, 256, 2, 4>(a, s);
-    return launch_big<256, 128, 4, 2>(a, s);
+    switch (big_tile_choice(a, num_cus)) {
+    case 1: return launch_big<256, 256, 2, 4>(a, s);
+    case 2: return launch_big<256, 128, 4, 2>(a, s);
+    case 3: return launch_big<128, 128, 2, 4>(a, s);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace rec

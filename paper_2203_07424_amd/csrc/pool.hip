@@ -12,7 +12,9 @@
 //
 // Bags of a few ids (one lookup per table and no pooling, Table I row MT-WnD)
 // would leave most of such a wave idle: pool_short_kernel gives each group of
-// LPR lanes a bag of its own, RPW bags per wave.
+// LPR lanes a bag of its own, RPW bags per wave.  (Giving bags of 20-50 ids, the
+// DLRM-RMC3 range of Table I, 4 * LPR lanes each was measured too: slower than
+// one wave per bag.)
 //
 // In the concatenation model the sums go, narrowed to bf16, straight into the
 // Predict-FC input row of their sample (concatenation and conversion fused,

@@ -497,3 +497,29 @@ def test_gradient_search_on_measured_throughput(binding):
     for m in models:
         assert m.check() == (binding.REC_OK, -1)
         m.close()
+
+
+@pytest.mark.parametrize("F,B", [(200, 3000), (203, 3000), (512, 3100)])
+def test_wide_bottom_layer_on_fp32_input(binding, F, B):
+    # A first Bottom-FC layer wide enough, on a batch large enough, for the
+    # 128 x 128 double-buffered tile that reads the fp32 dense input directly:
+    # F = 200 ends inside a k-tile (the rest must count as zero), F = 203 is not a
+    # multiple of 8 (the general kernel takes it), B is not a multiple of the tile.
+    say("wide bottom", F, B)
+    g = np.random.default_rng(300 + F)
+    T, R, D = 3, 200, 32
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(np.float32) for _ in range(T)]
+    lens = g.integers(0, 6, T * B).astype(np.int32)
+    idx = g.integers(0, R, int(lens.sum())).astype(np.int32)
+    bottom, top = small_mlps(g, F, D, T, (1024,), (64,))
+    dense = g.standard_normal((B, F)).astype(np.float32)
+    m = H.make_model(binding, tabs, bottom, top, B, idx.size, F)
+    logits = H.run(m, synth.Batch(dense, idx, lens))
+    assert m.check() == (binding.REC_OK, -1)
+    exact = orc.forward(dense, tabs, idx, lens, bottom, top, orc.EXACT)
+    mirror = orc.forward(dense, tabs, idx, lens, bottom, top, orc.BF16_MIRROR)
+    x0 = m.debug_bottom_out().cpu().numpy().astype(np.float64)
+    scale = np.abs(mirror["bottom_out"]).max() + 1e-30
+    assert np.abs(x0 - mirror["bottom_out"]).max() <= 2e-3 * scale
+    H.check_logits(logits, exact["logits"], mirror["logits"])
+    m.close()
