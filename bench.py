@@ -241,7 +241,7 @@ def search_mode(args) -> int:
     data = {}
     for B in sizes:
         w = w0.with_batch(B)
-        outs = [torch.empty(B, dtype=torch.float32, device=dev) for _ in counts]
+        outs = [new_logits(torch, w, B, dev) for _ in counts]
         data[B] = []
         for i in range(2):
             b = synth.draw_batch(w, 2000 + i, cdf)

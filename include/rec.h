@@ -142,7 +142,8 @@ REC_API size_t rec_workspace_bytes(const rec_model *m);
 /* Hands the model its workspace: dev_ptr is 256-byte aligned device memory of
  * at least rec_workspace_bytes().  Clears the device error record on `stream`
  * and waits for it; the first call also creates the library's side stream and
- * its two ordering events on the current device.  REC_ERR_ARG if too small or
+ * its two ordering events on the current device, and every call sets the
+ * kernels' LDS limits there (so: not under stream capture).  REC_ERR_ARG if too small or
  * misaligned. */
 REC_API rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *stream);
 
@@ -161,6 +162,7 @@ REC_API rec_status rec_load_tables(rec_model *m, int32_t table, const void *dev_
  * copy of the listed rows in LDS, refreshed from the table on every forward,
  * and serves lookups of those ids from there; the pooled sums are the same.
  * Ids listed twice or outside the table are ignored.  n = 0 removes the list.
+ * REC_INTERACT_CONCAT models accept the lists and ignore them.
  * REC_ERR_ARG if n > REC_MAX_HOT_ROWS or n rows do not fit the 64 KB LDS
  * budget (about 384 rows of 128 bytes); REC_ERR_STATE without a workspace. */
 REC_API rec_status rec_load_hot_rows(rec_model *m, int32_t table, const int32_t *dev_ids, int32_t n);

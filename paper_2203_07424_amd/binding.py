@@ -263,6 +263,14 @@ class RecModel:
         if logits is None:
             shape = (batch,) if self.towers == 1 else (batch, self.towers)
             logits = torch.empty(shape, dtype=torch.float32, device=self.device)
+        # The library sees pointers only: check here that every buffer is as large
+        # as the call says, of the right type, contiguous and on the device.
+        for name, t, dt, n in (("dense", dense, torch.float32, batch * self.F),
+                               ("indices", indices, torch.int32, indices.numel()),
+                               ("lengths", lengths, torch.int32, self.T * batch),
+                               ("logits", logits, torch.float32, batch * self.towers)):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and t.numel() >= n):
+                raise ValueError(f"rec_forward: {name} must be a contiguous {dt} device tensor of at least {n} elements")
         self._ok(rec_forward(self.handle, dense, indices, lengths, batch, indices.numel(), logits),
                  "rec_forward")
         self.last_batch = batch

@@ -259,14 +259,6 @@ hipError_t launch_big_as(const FcProblem &a, hipStream_t s)
     const dim3 grid(tiles * a.groups), block(64 * WAVES_M * WAVES_N);
     constexpr size_t lds = big_lds_bytes<BM, BN>();
     auto k = fc_big_kernel<BM, BN, WAVES_M, WAVES_N, A_F32, OUT_F32>;
-    // More than 64 KB of dynamic LDS has to be granted once per kernel.
-    static bool granted = false;
-    if (lds > 64 * 1024 && !granted) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        granted = true;
-    }
     hipLaunchKernelGGL(k, grid, block, lds, s, a.A, a.lda, a.a_stride, a.M, a.K, a.Kpad, a.g,
                        a.relu ? 1 : 0, a.C, a.ldc, a.c_stride, grid_m, grid_n, tiles);
     return hipGetLastError();
@@ -281,6 +273,24 @@ hipError_t launch_big(const FcProblem &a, hipStream_t s)
     }
     if (a.out_f32) return launch_big_as<BM, BN, WAVES_M, WAVES_N, false, true>(a, s);
     return launch_big_as<BM, BN, WAVES_M, WAVES_N, false, false>(a, s);
+}
+
+// More than 64 KB of dynamic LDS has to be granted to a kernel before its first launch.
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+hipError_t grant_lds()
+{
+    constexpr size_t lds = big_lds_bytes<BM, BN>();
+    if (lds <= 64 * 1024) return hipSuccess;
+    const void *kernels[4] = {
+        reinterpret_cast<const void *>(fc_big_kernel<BM, BN, WAVES_M, WAVES_N, false, false>),
+        reinterpret_cast<const void *>(fc_big_kernel<BM, BN, WAVES_M, WAVES_N, false, true>),
+        reinterpret_cast<const void *>(fc_big_kernel<BM, BN, WAVES_M, WAVES_N, true, false>),
+        reinterpret_cast<const void *>(fc_big_kernel<BM, BN, WAVES_M, WAVES_N, true, true>)};
+    for (const void *k : kernels) {
+        const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // Which block tile, if any: 256 x 256, 256 x 128 (bf16 input) or 128 x 128, the
@@ -302,6 +312,14 @@ int big_tile_choice(const FcProblem &a, int num_cus)
 }  // namespace
 
 bool fc_big_applies(const FcProblem &a, int num_cus) { return big_tile_choice(a, num_cus) != 0; }
+
+hipError_t fc_big_prepare()
+{
+    hipError_t e = grant_lds<256, 256, 2, 4>();
+    if (e == hipSuccess) e = grant_lds<256, 128, 4, 2>();
+    if (e == hipSuccess) e = grant_lds<128, 128, 2, 4>();
+    return e;
+}
 
 hipError_t launch_fc_big(const FcProblem &a, int num_cus, hipStream_t s)
 {

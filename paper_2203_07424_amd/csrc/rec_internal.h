@@ -98,6 +98,9 @@ hipError_t launch_fc(const FcProblem &p, hipStream_t s);
 // launch_fc() takes this path by itself when fc_big_applies().
 bool fc_big_applies(const FcProblem &p, int num_cus);
 hipError_t launch_fc_big(const FcProblem &p, int num_cus, hipStream_t s);
+// Once per process and device, before the first launch (not under stream
+// capture): lets these kernels use their more-than-64-KB LDS tiles.
+hipError_t fc_big_prepare();
 
 // Last Predict-FC layer of every stack: logits[m * ld + g] = sum_k A_g[m][k] * w_g[k] + bias_g[0]
 // in fp32.  A_g = A + g * a_stride is fp32 [M][lda] (a_f32) or bf16 [M][lda];

@@ -232,3 +232,45 @@ def test_wide_tower_layers_on_ragged_batches(binding, hidden, towers, B):
     mirror = orc.forward_towers(dense, tabs, idx, lens, bottom, tw, orc.BF16_MIRROR)
     H.check_logits(logits, exact["logits"], mirror["logits"])
     m.close()
+
+
+def test_tower_model_graph_replay_overlap_and_repeatability(binding):
+    """The tower model under a HIP graph (large batch, so the wide-tile kernels
+    and their more-than-64-KB LDS grant are inside the capture), with the
+    Bottom-FC on the side stream, and run twice: all must give the same bits."""
+    say("towers: graph, overlap, repeatability")
+    g = np.random.default_rng(93)
+    T, R, D, B, F = 6, 300, 32, 1100, 16
+    tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(np.float16) for _ in range(T)]
+    bottom, towers = stacks(g, F, (48, 24), T, D, (1280, 64), 8)
+    m = H.make_model(binding, tabs, bottom, towers, B, T * B, F, interaction="concat")
+
+    def draw():
+        return synth.Batch(g.standard_normal((B, F)).astype(np.float32),
+                           g.integers(0, R, T * B).astype(np.int32), np.ones(T * B, np.int32))
+    first = draw()
+    eager0 = H.run(m, first)
+    assert np.array_equal(eager0, H.run(m, first))                    # run to run
+    m.set_option(binding.REC_OPT_OVERLAP_DENSE, 1)
+    assert np.array_equal(eager0, H.run(m, first))                    # side stream
+    m.set_option(binding.REC_OPT_OVERLAP_DENSE, 0)
+    bufs = (torch.from_numpy(first.dense).cuda(), torch.from_numpy(first.indices).cuda(),
+            torch.from_numpy(first.lengths).cuda())
+    out = torch.empty((B, 8), dtype=torch.float32, device="cuda")
+    cap = binding.CapturedForward(m, [bufs], [out])
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for rep in range(4):
+        b = first if rep == 0 else draw()
+        bufs[0].copy_(torch.from_numpy(b.dense))
+        bufs[1].copy_(torch.from_numpy(b.indices))
+        out.zero_()
+        cap.replay()
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().copy()
+        scratch.add_(1.0)
+        assert np.array_equal(got, H.run(m, b)), rep
+        assert m.check() == (binding.REC_OK, -1)
+    exact = orc.forward_towers(b.dense, tabs, b.indices, b.lengths, bottom, towers)
+    mirror = orc.forward_towers(b.dense, tabs, b.indices, b.lengths, bottom, towers, orc.BF16_MIRROR)
+    H.check_logits(got, exact["logits"], mirror["logits"])
+    m.close()
