@@ -274,3 +274,41 @@ def test_tower_model_graph_replay_overlap_and_repeatability(binding):
     mirror = orc.forward_towers(b.dense, tabs, b.indices, b.lengths, bottom, towers, orc.BF16_MIRROR)
     H.check_logits(got, exact["logits"], mirror["logits"])
     m.close()
+
+
+@pytest.mark.parametrize("interaction", ["dot", "concat"])
+def test_batch_without_any_id(binding, interaction):
+    # Every bag empty: nnz = 0 and no index buffer at all.  The embeddings'
+    # share of the Predict-FC input is zero, the logits depend on the dense part only.
+    say("no ids", interaction)
+    g = np.random.default_rng(95)
+    T, R, D, B, F = 3, 50, 32, 70, 32
+    tabs = [g.uniform(-1, 1, (R, D)).astype(np.float32) for _ in range(T)]
+    lens = np.zeros(T * B, dtype=np.int32)
+    idx = np.zeros(0, dtype=np.int32)
+    dense = g.standard_normal((B, F)).astype(np.float32)
+    if interaction == "concat":
+        bottom, top = stacks(g, F, (), T, D, (48,), 2)
+        oracle = lambda mode: orc.forward_towers(dense, tabs, idx, lens, bottom, top, mode)
+    else:
+        bottom = []
+        width = D + T * (T + 1) // 2
+        top = [((g.standard_normal((40, width)) * width ** -0.5).astype(np.float32), np.zeros(40, np.float32)),
+               ((g.standard_normal((1, 40)) * 40 ** -0.5).astype(np.float32), np.ones(1, np.float32))]
+        oracle = lambda mode: orc.forward(dense, tabs, idx, lens, bottom, top, mode)
+    m = H.make_model(binding, tabs, bottom, top, B, 16, F, interaction=interaction)
+    d = torch.from_numpy(dense).cuda()
+    l = torch.from_numpy(lens).cuda()
+    out = torch.empty((B, 2) if interaction == "concat" else (B,), dtype=torch.float32, device="cuda")
+    assert binding.rec_forward(m.handle, d, None, l, B, 0, out) == binding.REC_OK
+    torch.cuda.synchronize()
+    m.last_batch = B
+    assert m.check() == (binding.REC_OK, -1)
+    assert not m.debug_offsets().cpu().numpy().any()
+    z = m.debug_interact().float().cpu().numpy()
+    w0 = F if interaction == "concat" else D
+    assert not z[:, w0:].any()                      # embeddings and every dot with them: zero
+    got = out.cpu().numpy()
+    exact, mirror = oracle(orc.EXACT), oracle(orc.BF16_MIRROR)
+    H.check_logits(got, exact["logits"], mirror["logits"])
+    m.close()
