@@ -34,17 +34,20 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 
 # HBM traffic of one pooling launch from rocprofv3 counter runs (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy: 2.000 and
-# 1.000), see profiles/pool_rmc2_counters.md.  Valid only for the kernel source
+# 1.000), see profiles/pool_rmc2_counters.md; Zipf ids with cached row loads,
+# the uniform twin with non-temporal ones (what --stream-rows auto picks).  Valid only for the kernel source
 # the counters were taken with; reported as null once csrc/pool.hip differs.
 POOL_TRAFFIC = {
-    "sha256": "680f2f51f71ac0892450fadb6eba28c109aec36ac9fbc6fe3ff288003977ec47",
-    ("rmc2", 4096): {"fetch_bytes": 554025732.0, "write_bytes": 41943040.0},
-    ("rmc2-uniform", 4096): {"fetch_bytes": 1707531372.0, "write_bytes": 41943237.0},
+    "sha256": "2da94a5c5bbce6b318ea68380cb0e741a800ca3ca78ea47148faa96f8bf95e9f",
+    ("rmc2", 4096): {"fetch_bytes": 554032620.0, "write_bytes": 41943050.0},
+    ("rmc2-uniform", 4096): {"fetch_bytes": 1721983595.0, "write_bytes": 41943099.0},
 }
 
 
-def measured_pool_traffic(w):
+def measured_pool_traffic(w, streaming):
     import hashlib
+    if streaming != (w.index_dist[0] == "uniform"):   # the counters were taken with the automatic choice
+        return None
     src = os.path.join(ROOT, "paper_2203_07424_amd", "csrc", "pool.hip")
     rec = POOL_TRAFFIC.get((w.name, w.batch))
     if rec is None or not os.path.exists(src):
@@ -311,6 +314,9 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="record the distinct batches' forwards into one HIP graph and replay "
                          "it (steps are rounded to whole replays; no stage events)")
+    ap.add_argument("--stream-rows", choices=["auto", "on", "off"], default="auto",
+                    help="pooling loads table rows with the non-temporal hint; auto = only for "
+                         "workloads whose ids are drawn uniformly (no reuse for the caches to serve)")
     ap.add_argument("--overlap", action="store_true",
                     help="run Bottom-FC on the library's side stream beside scan and pooling")
     ap.add_argument("--event-period", type=int, default=10,
@@ -360,6 +366,11 @@ def main() -> int:
     if args.overlap:
         for mm in models:
             mm.set_option(binding.REC_OPT_OVERLAP_DENSE, 1)
+
+    def wants_streaming(wl):
+        return args.stream_rows == "on" or (args.stream_rows == "auto" and wl.index_dist[0] == "uniform")
+    for mm in models:
+        mm.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(w)))
     if args.hot_rows > 0:
         pcdf = synth.zipf_cdf(w.rows, float(w.index_dist[1])) if w.index_dist[0] == "zipf" else None
         hot = synth.profile_hot_rows(w, [900, 901], args.hot_rows, pcdf)
@@ -450,16 +461,17 @@ def main() -> int:
         achieved = pool_bytes / (avg["pool"] * 1e-3) / 1e9
         pool = {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm",
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_pool_traffic(wl),
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_pool_traffic(wl, wants_streaming(wl)),
                 "bytes_per_launch": pool_bytes, "avg_launch_ms": avg["pool"],
-                "launches_timed": count}
+                "launches_timed": count,
+                "row_loads": "non-temporal" if wants_streaming(wl) else "cached"}
         if wl.interaction != "concat":
             return avg, pool
         # Dense-dominated shape: the first Predict-FC layer of all towers is one
         # launch and the longest kernel; its algorithmic work is 2 * B * K * N per tower.
         flops = 2.0 * wl.batch * wl.top[0] * wl.top[1] * wl.towers
         tf = flops / (avg["top_first"] * 1e-3) / 1e12
-        return avg, {"kernel": "fc_kernel (first Predict-FC layer of all towers, one launch)",
+        return avg, {"kernel": "fc_big_kernel (first Predict-FC layer of all towers, one launch)",
                      "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "flops_per_launch": flops, "avg_launch_ms": avg["top_first"],
@@ -492,7 +504,9 @@ def main() -> int:
         if w.index_dist[0] == "zipf" and w.interaction == "dot":
             wu = w.with_uniform_indices()
             hbu, dbu = make_batches(wu, 2, 500)
+            m.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(wu)))
             st_u, rf_u = solo(dbu, hbu, wu)
+            m.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(w)))
             extra["roofline_uniform_ids"] = rf_u
             del dbu
 

@@ -16,6 +16,11 @@
 // DLRM-RMC3 range of Table I, 4 * LPR lanes each was measured too: slower than
 // one wave per bag.)
 //
+// STREAM: the rows are loaded with the non-temporal hint (they are not kept in
+// the caches ahead of other lines).  For id streams without reuse (uniform ids)
+// that is 2.5 % faster; for skewed ids, whose hot rows the caches serve, it is
+// 20 % slower, so it is an option the caller sets from what it knows of its ids.
+//
 // In the concatenation model the sums go, narrowed to bf16, straight into the
 // Predict-FC input row of their sample (concatenation and conversion fused,
 // Sec. IV-A) instead of the fp32 pooled buffer.
@@ -92,7 +97,7 @@ __device__ inline void store_sums(const Acc<HALF> &acc, const PoolOut &out, int 
     }
 }
 
-template <int LPR, bool HALF, bool CONCAT>
+template <int LPR, bool HALF, bool CONCAT, bool STREAM>
 __global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
     const TableDesc *__restrict__ tables, const int32_t *__restrict__ indices,
     const int32_t *__restrict__ offsets, const PoolOut out, int vec_ok, int B, int T, int nbags,
@@ -152,7 +157,8 @@ __global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
                 const int id = __shfl(cur, slot & 63, 64);
                 ok[u] = (j + u) < steps && id >= 0;
                 const long long row = ok[u] ? id : 0;
-                raw[u] = *reinterpret_cast<const f32x4 *>(lane_base + row * ROWBYTES);
+                const f32x4 *src = reinterpret_cast<const f32x4 *>(lane_base + row * ROWBYTES);
+                raw[u] = STREAM ? __builtin_nontemporal_load(src) : *src;
             }
 #pragma unroll
             for (int u = 0; u < POOL_UNROLL; ++u) accumulate<HALF>(acc, raw[u], ok[u]);
@@ -224,7 +230,7 @@ __global__ __launch_bounds__(POOL_WAVES * 64) void pool_short_kernel(
 }
 
 template <int LPR, bool HALF, bool CONCAT>
-hipError_t launch_shape(bool short_bags, const TableDesc *tables, int T, int B, const int32_t *indices,
+hipError_t launch_shape(bool short_bags, bool stream_rows, const TableDesc *tables, int T, int B, const int32_t *indices,
                         const int32_t *offsets, const PoolOut &out, ErrRecord *err, hipStream_t s)
 {
     constexpr int NACC = HALF ? 8 : 4;
@@ -238,43 +244,47 @@ hipError_t launch_shape(bool short_bags, const TableDesc *tables, int T, int B, 
                            offsets, out, vec_ok, B, T, nbags, err);
     } else {
         const dim3 grid(((nbags + POOL_WAVES - 1) / POOL_WAVES + 7) / 8 * 8);
-        hipLaunchKernelGGL((pool_kernel<LPR, HALF, CONCAT>), grid, block, 0, s, tables, indices, offsets,
-                           out, vec_ok, B, T, nbags, err);
+        if (stream_rows)
+            hipLaunchKernelGGL((pool_kernel<LPR, HALF, CONCAT, true>), grid, block, 0, s, tables, indices,
+                               offsets, out, vec_ok, B, T, nbags, err);
+        else
+            hipLaunchKernelGGL((pool_kernel<LPR, HALF, CONCAT, false>), grid, block, 0, s, tables, indices,
+                               offsets, out, vec_ok, B, T, nbags, err);
     }
     return hipGetLastError();
 }
 
 template <int LPR>
-hipError_t launch_lpr(bool half, bool short_bags, const TableDesc *tables, int T, int B,
+hipError_t launch_lpr(bool half, bool short_bags, bool stream_rows, const TableDesc *tables, int T, int B,
                       const int32_t *indices, const int32_t *offsets, const PoolOut &out, ErrRecord *err,
                       hipStream_t s)
 {
     if (out.z) {
-        if (half) return launch_shape<LPR, true, true>(short_bags, tables, T, B, indices, offsets, out, err, s);
-        return launch_shape<LPR, false, true>(short_bags, tables, T, B, indices, offsets, out, err, s);
+        if (half) return launch_shape<LPR, true, true>(short_bags, stream_rows, tables, T, B, indices, offsets, out, err, s);
+        return launch_shape<LPR, false, true>(short_bags, stream_rows, tables, T, B, indices, offsets, out, err, s);
     }
-    if (half) return launch_shape<LPR, true, false>(short_bags, tables, T, B, indices, offsets, out, err, s);
-    return launch_shape<LPR, false, false>(short_bags, tables, T, B, indices, offsets, out, err, s);
+    if (half) return launch_shape<LPR, true, false>(short_bags, stream_rows, tables, T, B, indices, offsets, out, err, s);
+    return launch_shape<LPR, false, false>(short_bags, stream_rows, tables, T, B, indices, offsets, out, err, s);
 }
 
 }  // namespace
 
 hipError_t launch_pool(const TableDesc *tables, int dtype, int T, int D, int B,
                        const int32_t *indices, const int32_t *offsets, PoolOut out, long long nnz,
-                       ErrRecord *err, hipStream_t s)
+                       bool stream_rows, ErrRecord *err, hipStream_t s)
 {
     if (T <= 0 || B <= 0) return hipSuccess;
     const bool half = dtype == REC_F16;
     const int rowbytes = D * (half ? 2 : 4);
     const bool sh = rowbytes < 1024 && nnz <= (long long)SHORT_MEAN * T * B;
     switch (rowbytes / 16) {
-    case 1: return launch_lpr<1>(half, sh, tables, T, B, indices, offsets, out, err, s);
-    case 2: return launch_lpr<2>(half, sh, tables, T, B, indices, offsets, out, err, s);
-    case 4: return launch_lpr<4>(half, sh, tables, T, B, indices, offsets, out, err, s);
-    case 8: return launch_lpr<8>(half, sh, tables, T, B, indices, offsets, out, err, s);
-    case 16: return launch_lpr<16>(half, sh, tables, T, B, indices, offsets, out, err, s);
-    case 32: return launch_lpr<32>(half, sh, tables, T, B, indices, offsets, out, err, s);
-    case 64: return launch_lpr<64>(half, sh, tables, T, B, indices, offsets, out, err, s);
+    case 1: return launch_lpr<1>(half, sh, stream_rows, tables, T, B, indices, offsets, out, err, s);
+    case 2: return launch_lpr<2>(half, sh, stream_rows, tables, T, B, indices, offsets, out, err, s);
+    case 4: return launch_lpr<4>(half, sh, stream_rows, tables, T, B, indices, offsets, out, err, s);
+    case 8: return launch_lpr<8>(half, sh, stream_rows, tables, T, B, indices, offsets, out, err, s);
+    case 16: return launch_lpr<16>(half, sh, stream_rows, tables, T, B, indices, offsets, out, err, s);
+    case 32: return launch_lpr<32>(half, sh, stream_rows, tables, T, B, indices, offsets, out, err, s);
+    case 64: return launch_lpr<64>(half, sh, stream_rows, tables, T, B, indices, offsets, out, err, s);
     default: return hipErrorInvalidValue;
     }
 }

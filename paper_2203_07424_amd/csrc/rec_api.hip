@@ -53,6 +53,7 @@ struct rec_model {
 
     // Bottom-FC runs on a stream of the library's own, beside scan and pooling.
     bool overlap_dense = false;
+    bool stream_rows = false;  // pooling loads rows with the non-temporal hint
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
@@ -382,7 +383,7 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
             const PoolOut out = concat ? PoolOut{nullptr, act[0], m->z_ld, m->w0}
                                        : PoolOut{pooled, nullptr, 0, 0};
             REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
-                                out, nnz, err, s));
+                                out, nnz, m->stream_rows, err, s));
         }
     }
     REC_MARK();
@@ -496,6 +497,7 @@ rec_status rec_set_option(rec_model *m, int32_t option, int32_t value)
     if (!m) return REC_ERR_ARG;
     switch (option) {
     case REC_OPT_OVERLAP_DENSE: m->overlap_dense = value != 0; return REC_OK;
+    case REC_OPT_STREAM_ROWS: m->stream_rows = value != 0; return REC_OK;
     default: return REC_ERR_ARG;
     }
 }

@@ -93,6 +93,30 @@ def test_offsets_bit_exact_and_pooling_within_tolerance(binding, T, R, D, dtype,
     m.close()
 
 
+def test_streaming_row_loads_give_the_same_sums(binding):
+    # The non-temporal hint changes where rows are cached, not what is summed.
+    say("streaming rows")
+    g = np.random.default_rng(61)
+    for (T, R, D, dtype, B) in [(3, 2000, 64, np.float16, 300), (2, 500, 32, np.float32, 129), (1, 300, 256, np.float32, 17)]:
+        tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(dtype) for _ in range(T)]
+        lens = g.integers(0, 150, T * B).astype(np.int32)
+        idx = g.integers(0, R, int(lens.sum())).astype(np.int32)
+        bottom, top = small_mlps(g, 4, D, T)
+        dense = g.standard_normal((B, 4)).astype(np.float32)
+        m = H.make_model(binding, tabs, bottom, top, B, idx.size, 4)
+        batch = synth.Batch(dense, idx, lens)
+        cached = H.run(m, batch)
+        pooled_cached = m.debug_pooled().cpu().numpy()
+        m.set_option(binding.REC_OPT_STREAM_ROWS, 1)
+        streamed = H.run(m, batch)
+        assert np.array_equal(pooled_cached, m.debug_pooled().cpu().numpy())
+        assert np.array_equal(cached, streamed)
+        P, A, nbad, _ = orc.pool(tabs, idx, lens, B, want_abs=True)
+        H.check_pooled(m.debug_pooled().cpu().numpy(), P, A)
+        assert m.check() == (binding.REC_OK, -1)
+        m.close()
+
+
 def test_pooling_closed_forms_on_device(binding):
     say("pool closed forms")
     g = np.random.default_rng(7)
