@@ -289,7 +289,7 @@ def search_mode(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="rmc2")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
