@@ -91,7 +91,20 @@ def cpu_baseline(w, batches, bottom, top, n_samples: int) -> dict:
             orc.forward(sub.dense, tabs, cidx, sub.lengths, bottom, top)
         dt += time.perf_counter() - t0
     total = n_samples * len(batches)
+    # one thread, on a smaller slice, for the per-core rate
+    n1 = min(256, n_samples)
+    sub = synth.slice_samples(w, batches[0], np.arange(n1))
+    tabs, cidx = synth.compact_tables(w, sub, n1)
+    orc.set_threads(1)
+    t0 = time.perf_counter()
+    if w.interaction == "concat":
+        orc.forward_towers(sub.dense, tabs, cidx, sub.lengths, bottom, top)
+    else:
+        orc.forward(sub.dense, tabs, cidx, sub.lengths, bottom, top)
+    dt1 = time.perf_counter() - t0
+    orc.set_threads(threads)
     return {"value": total / dt, "unit": "samples/s", "cores": threads, "kind": "oracle",
+            "single_thread": {"value": n1 / dt1, "unit": "samples/s", "sample": f"first {n1} samples of batch 0, {dt1:.2f} s"},
             "sample": f"first {n_samples} samples of each of {len(batches)} batches of {w.name} (rows they "
                       f"touch materialised in compact tables, which is not timed), whole forward, "
                       f"{dt:.2f} s wall on {threads} threads"}
@@ -536,6 +549,23 @@ def main() -> int:
                                "steps": args.steps}
         for mm in cm[1:]:
             mm.close()
+
+    # What a plain device-to-device copy reaches on this machine (bytes read + written),
+    # the practical yardstick beside the published peak.
+    if use_events and not args.graph:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        extra["device_copy_gbps"] = 5 * 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del src, dst
 
     cpu = None
     if not args.no_cpu_baseline:
