@@ -490,11 +490,27 @@ def main() -> int:
                      "flops_per_launch": flops, "avg_launch_ms": avg["top_first"],
                      "launches_timed": count, "pooling": pool}
 
+    def mlp_mfma(wl, avg):
+        """Matrix-unit use of the MLP stages: unpadded 2*M*N*K of the stage's layers over
+        its HIP-event interval (which includes one event record and, for small
+        layers, mostly launch latency) against the bf16 MFMA peak."""
+        def flops(widths):
+            return sum(2.0 * wl.batch * widths[i] * widths[i + 1] for i in range(len(widths) - 1))
+        out = {}
+        for stage, widths, mult in (("bottom", wl.bottom, 1), ("top_first", wl.top[:2], wl.towers),
+                                    ("top_rest", wl.top[1:], wl.towers)):
+            f = flops(widths) * mult
+            if f > 0 and avg[stage] > 0:
+                tf = f / (avg[stage] * 1e-3) / 1e12
+                out[stage] = {"gflop": f / 1e9, "tflops": tf, "frac_of_bf16_peak": tf / MFMA_BF16_PEAK_TFLOPS}
+        return out
+
     stage_avg = roofline = None
     if use_events:
         used = [host_batches[(j * args.event_period * n_inst) % len(host_batches)] for j in range(n_timed)]
         stage_avg, roofline = collect(m, n_timed, used, w)
         roofline["instances_sharing_the_gpu"] = n_inst
+        extra_mlp = mlp_mfma(w, stage_avg)
 
     # Two short extra legs, one instance alone on the GPU, every step bracketed:
     # the same workload, and its uniform-id twin (no cache reuse: the run on
@@ -587,6 +603,7 @@ def main() -> int:
                    "co_located_instances": n_inst, "hip_graph": bool(args.graph), "hot_rows_per_table": args.hot_rows,
                    "mean_nnz": float(np.mean([b.nnz for b in host_batches]))},
         "roofline": roofline, "cpu_baseline": cpu, "stage_ms": stage_avg,
+        "mlp_mfma": extra_mlp if use_events else None,
     }
     out.update(extra)
     print(json.dumps(out), flush=True)
