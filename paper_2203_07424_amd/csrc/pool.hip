@@ -37,6 +37,7 @@ constexpr int POOL_WAVES = 4;   // bags per block
 constexpr int POOL_UNROLL = 4;  // row loads in flight per lane and step
 
 constexpr int SHORT_UNROLL = 4;  // row loads in flight per lane in the short-bag kernel
+constexpr int SHORT_BAGS = 2;    // bags a group of lanes works on at a time
 constexpr int SHORT_MEAN = 4;    // mean ids per bag up to which bags share a wave
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -174,59 +175,85 @@ __global__ __launch_bounds__(POOL_WAVES * 64) void pool_kernel(
     if (sub == 0) store_sums<HALF, CONCAT>(acc, out, vec_ok, b, t, T, D, chunk);
 }
 
-// One bag per group of LPR lanes.  Lanes past the last bag work on a copy of it
-// and store nothing.
+// SHORT_BAGS bags per group of LPR lanes, their load chains (offsets -> ids ->
+// rows) running side by side; group g of the launch takes bags g, g + groups,
+// ...  Slots past the last bag work on a copy of it and store nothing.
 template <int LPR, bool HALF, bool CONCAT>
 __global__ __launch_bounds__(POOL_WAVES * 64) void pool_short_kernel(
     const TableDesc *__restrict__ tables, const int32_t *__restrict__ indices,
     const int32_t *__restrict__ offsets, const PoolOut out, int vec_ok, int B, int T, int nbags,
-    ErrRecord *err)
+    int groups, ErrRecord *err)
 {
     constexpr int RPW = 64 / LPR;
     constexpr int ROWBYTES = LPR * 16;
     constexpr int NACC = HALF ? 8 : 4;
     constexpr int D = ROWBYTES / (HALF ? 2 : 4);
+    constexpr int PER_BAG = SHORT_UNROLL / SHORT_BAGS;  // row loads in flight per bag
 
     const int lane = threadIdx.x & 63;
     const int sub = lane / LPR, chunk = lane % LPR;
     const int per = gridDim.x >> 3;
     const int vblk = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-    const long long slot = ((long long)vblk * POOL_WAVES + (threadIdx.x >> 6)) * RPW + sub;
-    const bool live = slot < nbags;
-    const int bag = live ? (int)slot : nbags - 1;
-    const int t = bag / B;
-    const int b = bag - t * B;
-    const int start = offsets[bag];
-    const int end = live ? offsets[bag + 1] : start;
-    const char *lane_base = static_cast<const char *>(tables[t].base) + chunk * 16;
-    const long long rows = tables[t].rows;
+    const long long group = ((long long)vblk * POOL_WAVES + (threadIdx.x >> 6)) * RPW + sub;
 
-    Acc<HALF> acc;
+    bool live[SHORT_BAGS];
+    int t[SHORT_BAGS], b[SHORT_BAGS], pos[SHORT_BAGS], end[SHORT_BAGS];
+    const char *lane_base[SHORT_BAGS];
+    long long rows[SHORT_BAGS];
+    Acc<HALF> acc[SHORT_BAGS];
 #pragma unroll
-    for (int i = 0; i < NACC; ++i) acc.v[i] = 0.0f;
-
-    for (int k0 = start; k0 < end; k0 += SHORT_UNROLL) {
-        f32x4 raw[SHORT_UNROLL];
-        bool ok[SHORT_UNROLL];
+    for (int g = 0; g < SHORT_BAGS; ++g) {
+        const long long slot = group + (long long)g * groups;
+        live[g] = slot < nbags;
+        const int bag = live[g] ? (int)slot : nbags - 1;
+        t[g] = bag / B;
+        b[g] = bag - t[g] * B;
+        pos[g] = offsets[bag];
+        end[g] = live[g] ? offsets[bag + 1] : pos[g];
+        lane_base[g] = static_cast<const char *>(tables[t[g]].base) + chunk * 16;
+        rows[g] = tables[t[g]].rows;
 #pragma unroll
-        for (int u = 0; u < SHORT_UNROLL; ++u) {
-            const int k = k0 + u;
-            const int id = indices[k < end ? k : end - 1];
-            ok[u] = k < end;
-            if (ok[u] && (unsigned long long)(long long)id >= (unsigned long long)rows) {
-                if (chunk == 0) {
-                    atomicMin(&err->first_bad_idx, (unsigned long long)k);
-                    atomicOr(&err->flags, ERR_INDEX_RANGE);
-                }
-                ok[u] = false;
-            }
-            const long long row = ok[u] ? id : 0;
-            raw[u] = *reinterpret_cast<const f32x4 *>(lane_base + row * ROWBYTES);
-        }
-#pragma unroll
-        for (int u = 0; u < SHORT_UNROLL; ++u) accumulate<HALF>(acc, raw[u], ok[u]);
+        for (int i = 0; i < NACC; ++i) acc[g].v[i] = 0.0f;
     }
-    if (live) store_sums<HALF, CONCAT>(acc, out, vec_ok, b, t, T, D, chunk);
+
+    bool more = false;
+#pragma unroll
+    for (int g = 0; g < SHORT_BAGS; ++g) more |= pos[g] < end[g];
+    while (more) {
+        f32x4 raw[SHORT_BAGS][PER_BAG];
+        bool ok[SHORT_BAGS][PER_BAG];
+#pragma unroll
+        for (int g = 0; g < SHORT_BAGS; ++g) {
+#pragma unroll
+            for (int u = 0; u < PER_BAG; ++u) {
+                const int k = pos[g] + u;
+                ok[g][u] = k < end[g];
+                // positions past the bag re-read its last id (or, for an empty bag, nothing: id 0)
+                const int kk = ok[g][u] ? k : (end[g] > 0 ? end[g] - 1 : 0);
+                const int id = pos[g] < end[g] ? indices[kk] : 0;
+                if (ok[g][u] && (unsigned long long)(long long)id >= (unsigned long long)rows[g]) {
+                    if (chunk == 0) {
+                        atomicMin(&err->first_bad_idx, (unsigned long long)k);
+                        atomicOr(&err->flags, ERR_INDEX_RANGE);
+                    }
+                    ok[g][u] = false;
+                }
+                const long long row = ok[g][u] ? id : 0;
+                raw[g][u] = *reinterpret_cast<const f32x4 *>(lane_base[g] + row * ROWBYTES);
+            }
+        }
+        more = false;
+#pragma unroll
+        for (int g = 0; g < SHORT_BAGS; ++g) {
+#pragma unroll
+            for (int u = 0; u < PER_BAG; ++u) accumulate<HALF>(acc[g], raw[g][u], ok[g][u]);
+            pos[g] = min(pos[g] + PER_BAG, end[g]);
+            more |= pos[g] < end[g];
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < SHORT_BAGS; ++g)
+        if (live[g]) store_sums<HALF, CONCAT>(acc[g], out, vec_ok, b[g], t[g], T, D, chunk);
 }
 
 template <int LPR, bool HALF, bool CONCAT>
@@ -238,10 +265,12 @@ hipError_t launch_shape(bool short_bags, bool stream_rows, const TableDesc *tabl
     const int vec_ok = CONCAT && out.col0 % NACC == 0 && reinterpret_cast<uintptr_t>(out.z) % 16 == 0;
     const dim3 block(POOL_WAVES * 64);
     if (short_bags) {
-        const int per_block = POOL_WAVES * (64 / LPR);
+        const int groups_per_block = POOL_WAVES * (64 / LPR);
+        const int per_block = groups_per_block * SHORT_BAGS;
         const dim3 grid(((nbags + per_block - 1) / per_block + 7) / 8 * 8);
+        const int groups = (int)grid.x * groups_per_block;
         hipLaunchKernelGGL((pool_short_kernel<LPR, HALF, CONCAT>), grid, block, 0, s, tables, indices,
-                           offsets, out, vec_ok, B, T, nbags, err);
+                           offsets, out, vec_ok, B, T, nbags, groups, err);
     } else {
         const dim3 grid(((nbags + POOL_WAVES - 1) / POOL_WAVES + 7) / 8 * 8);
         if (stream_rows)
