@@ -7,16 +7,20 @@
 // narrowed to bf16 and zero padded to the GEMM's leading dimension -
 // concatenation and conversion are fused here (Sec. IV-A, operator fusion).
 //
-// LDS-tiled: a block stages X of a few samples in LDS (16-byte columns of a
-// row XOR-swizzled by the row number, so that the 16 lanes that read 16
-// consecutive rows hit different banks).  The Gram matrix X X^T is a small
-// dense contraction and plain vector FMAs make it ALU-bound, so each wave
-// computes 16 x 16 tiles of it (blocks J <= I) with the fp32 matrix
-// instruction v_mfma_f32_16x16x4_f32: fp32 operands, fp32 accumulation, the
-// output's narrowing to bf16 is the only rounding.  Lane l feeds row l % 16 of
-// both operands and 4 consecutive k picked by l / 16 (one 16-byte LDS read per
-// operand serves four MFMAs).  Results are collected in LDS as one bf16 output
-// row per sample and written out with full 16-byte stores.
+// LDS-tiled: a block stages X of a few samples in LDS and each wave computes
+// 16 x 16 tiles of the Gram matrix X X^T (blocks J <= I) on the matrix cores.
+// The fp32 matrix instruction is slow (1/16 of the bf16 rate), and narrowing X
+// to bf16 would cost the interaction its fp32 accuracy, so X is split instead:
+// x = hi + lo with hi = bf16(x) and lo = bf16(x - hi), and
+//   <x, y> = <hi_x, hi_y> + <hi_x, lo_y> + <lo_x, hi_y>   (+ <lo_x, lo_y>, dropped: 2^-16 relative)
+// is three v_mfma_f32_16x16x32_bf16 per 32 k with fp32 accumulation.  hi + lo
+// carries 16 significant bits of x, so each product is good to about 2^-16
+// relative: far below the 2^-9 of the bf16 narrowing of the output, which stays
+// the only rounding that matters.  Lane l feeds row l % 16 of both operands and
+// the 8 consecutive k picked by l / 16.  The two planes sit in LDS with rows
+// padded by 16 bytes (conflict-free 16-byte reads of 16 consecutive rows).
+// Results are collected in LDS as one bf16 output row per sample and written
+// out with full 16-byte stores.
 #include "rec_internal.h"
 
 namespace rec {
@@ -25,6 +29,8 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int IT_THREADS = 256;
 constexpr int IT_WAVES = IT_THREADS / 64;
@@ -32,8 +38,8 @@ constexpr int IT_BATCH = 4;           // 16-byte loads in flight per thread whil
 constexpr int IT_TILES_PER_WAVE = 1;  // tiles a wave should get (sets the samples per block)
 
 struct Geometry {
-    int V, Vpad, nblk, ntile, d4, ksteps, swmask;
-    size_t x_floats;  // floats of X per sample
+    int V, Vpad, nblk, ntile, d4, dp, ld, ksteps;
+    size_t plane;  // elements of one bf16 plane (hi or lo) of X per sample
 };
 
 __host__ __device__ inline Geometry geometry(int T, int D)
@@ -44,14 +50,15 @@ __host__ __device__ inline Geometry geometry(int T, int D)
     g.Vpad = g.nblk * 16;
     g.ntile = g.nblk * (g.nblk + 1) / 2;
     g.d4 = D / 4;
-    g.ksteps = (g.d4 + 3) / 4;              // 16 k per step
-    g.swmask = (g.d4 < 8 ? g.d4 : 8) - 1;  // d4 is a power of two
-    g.x_floats = (size_t)g.Vpad * D;
+    g.dp = (D + 31) / 32 * 32;  // k extent, padded with zeros to whole MFMA steps
+    g.ld = g.dp + 8;            // padded row stride (elements)
+    g.ksteps = g.dp / 32;
+    g.plane = (size_t)g.Vpad * g.ld;
     return g;
 }
 
-// KSTEPS > 0 fixes the number of 16-wide k steps (D = 16 * KSTEPS) so that the
-// LDS reads of a tile are all issued before its MFMAs; 0 takes it at run time.
+// KSTEPS > 0 fixes the number of 32-wide k steps so that the LDS reads of a
+// tile are all issued before its MFMAs; 0 takes it at run time.
 template <int KSTEPS>
 __global__ __launch_bounds__(IT_THREADS) void interact_kernel(const float *__restrict__ x0, int ldx0,
                                                               const float *__restrict__ pooled,
@@ -59,48 +66,58 @@ __global__ __launch_bounds__(IT_THREADS) void interact_kernel(const float *__res
                                                               __bf16 *__restrict__ out, int ldo,
                                                               int spb)
 {
-    extern __shared__ __attribute__((aligned(16))) float s_mem[];
+    extern __shared__ __attribute__((aligned(16))) __bf16 s_mem[];
     const Geometry g = geometry(T, D);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b0 = blockIdx.x * spb;
     const int ns = min(spb, B - b0);  // samples of this block
-    float *sX = s_mem;                                                  // [spb][Vpad][D], swizzled
-    __bf16 *sO = reinterpret_cast<__bf16 *>(s_mem + (size_t)spb * g.x_floats);  // [spb][ldo]
+    __bf16 *sHi = s_mem;                             // [spb][Vpad][ld]
+    __bf16 *sLo = sHi + (size_t)spb * g.plane;       // [spb][Vpad][ld]
+    __bf16 *sO = sLo + (size_t)spb * g.plane;        // [spb][ldo]
 
-    // Stage X: row 0 = x0, rows 1..T = pooled (contiguous), rows V..Vpad = 0.
-    // d4 is a power of two, so rows and columns come from shifts; loads are
-    // issued IT_BATCH at a time before their LDS stores.
-    const int ld4 = __ffs(g.d4) - 1, n4 = g.Vpad << ld4;  // 16-byte words of X per sample
+    // Stage X: row 0 = x0, rows 1..T = pooled (contiguous), rows V..Vpad and the
+    // columns D..dp = 0.  A thread moves 4 consecutive columns at a time; loads
+    // are issued IT_BATCH at a time before their LDS stores.
+    const int c4n = g.dp / 4;             // 4-column groups per (padded) row
+    const int n4 = g.Vpad * c4n;          // ... per sample
     for (int s = 0; s < ns; ++s) {
         const long long b = b0 + s;
         const float *px0 = x0 + b * ldx0;
         const float *pp = pooled + b * T * D - D;  // row r >= 1 sits at pp + r * D
-        float *dst = sX + s * g.x_floats;
+        __bf16 *hi = sHi + s * g.plane, *lo = sLo + s * g.plane;
         for (int f0 = tid; f0 < n4; f0 += IT_BATCH * IT_THREADS) {
             f32x4 v[IT_BATCH];
 #pragma unroll
             for (int u = 0; u < IT_BATCH; ++u) {
                 const int f = f0 + u * IT_THREADS;
-                const int row = f >> ld4, c4 = f & (g.d4 - 1);
+                const int row = f / c4n, c4 = f - row * c4n;
                 v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-                if (f < n4 && row < g.V)
+                if (f < n4 && row < g.V && c4 < g.d4)
                     v[u] = *reinterpret_cast<const f32x4 *>((row == 0 ? px0 : pp + (size_t)row * D) + 4 * c4);
             }
 #pragma unroll
             for (int u = 0; u < IT_BATCH; ++u) {
                 const int f = f0 + u * IT_THREADS;
-                const int row = f >> ld4, c4 = f & (g.d4 - 1);
-                if (f < n4)
-                    *reinterpret_cast<f32x4 *>(dst + (size_t)row * D + 4 * (c4 ^ (row & g.swmask))) = v[u];
+                const int row = f / c4n, c4 = f - row * c4n;
+                if (f < n4) {
+                    bf16x4 h, l;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        h[i] = (__bf16)v[u][i];
+                        l[i] = (__bf16)(v[u][i] - (float)h[i]);
+                    }
+                    *reinterpret_cast<bf16x4 *>(hi + (size_t)row * g.ld + 4 * c4) = h;
+                    *reinterpret_cast<bf16x4 *>(lo + (size_t)row * g.ld + 4 * c4) = l;
+                }
             }
         }
     }
     __syncthreads();
 
-    // Dense part (row 0 is not displaced by the swizzle) and zero padding.
+    // Dense part (bf16(x0) is the hi plane of row 0) and zero padding.
     const int npairs = T * (T + 1) / 2, width = D + npairs;
     for (int s = 0; s < ns; ++s) {
-        for (int c = tid; c < D; c += IT_THREADS) sO[s * ldo + c] = (__bf16)sX[s * g.x_floats + c];
+        for (int c = tid; c < D; c += IT_THREADS) sO[s * ldo + c] = sHi[s * g.plane + c];
         for (int c = width + tid; c < ldo; c += IT_THREADS) sO[s * ldo + c] = (__bf16)0.0f;
     }
 
@@ -112,35 +129,34 @@ __global__ __launch_bounds__(IT_THREADS) void interact_kernel(const float *__res
         int I = 0;
         while ((I + 1) * (I + 2) / 2 <= tile) ++I;
         const int J = tile - I * (I + 1) / 2;
-        const int rowA = 16 * I + r16, rowB = 16 * J + r16;
-        const float *xa = sX + s * g.x_floats + (size_t)rowA * D;
-        const float *xb = sX + s * g.x_floats + (size_t)rowB * D;
-        const int swa = rowA & g.swmask, swb = rowB & g.swmask;
+        const size_t offA = s * g.plane + (size_t)(16 * I + r16) * g.ld + 8 * kq;
+        const size_t offB = s * g.plane + (size_t)(16 * J + r16) * g.ld + 8 * kq;
         f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
         if (KSTEPS > 0) {
-            f32x4 a[KSTEPS > 0 ? KSTEPS : 1], b[KSTEPS > 0 ? KSTEPS : 1];
+            bf16x8 ah[KSTEPS > 0 ? KSTEPS : 1], al[KSTEPS > 0 ? KSTEPS : 1], bh[KSTEPS > 0 ? KSTEPS : 1],
+                bl[KSTEPS > 0 ? KSTEPS : 1];
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
-                const int c4 = 4 * ks + kq;
-                a[ks] = *reinterpret_cast<const f32x4 *>(xa + 4 * (c4 ^ swa));
-                b[ks] = *reinterpret_cast<const f32x4 *>(xb + 4 * (c4 ^ swb));
+                ah[ks] = *reinterpret_cast<const bf16x8 *>(sHi + offA + 32 * ks);
+                al[ks] = *reinterpret_cast<const bf16x8 *>(sLo + offA + 32 * ks);
+                bh[ks] = *reinterpret_cast<const bf16x8 *>(sHi + offB + 32 * ks);
+                bl[ks] = *reinterpret_cast<const bf16x8 *>(sLo + offB + 32 * ks);
             }
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ks][v], b[ks][v], acc, 0, 0, 0);
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[ks], bh[ks], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bl[ks], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bh[ks], acc, 0, 0, 0);
+            }
         } else {
             for (int ks = 0; ks < g.ksteps; ++ks) {
-                const int c4 = 4 * ks + kq;
-                f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f}, b = a;
-                if (c4 < g.d4) {
-                    a = *reinterpret_cast<const f32x4 *>(xa + 4 * (c4 ^ swa));
-                    b = *reinterpret_cast<const f32x4 *>(xb + 4 * (c4 ^ swb));
-                }
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[v], b[v], acc, 0, 0, 0);
+                const bf16x8 ah = *reinterpret_cast<const bf16x8 *>(sHi + offA + 32 * ks);
+                const bf16x8 al = *reinterpret_cast<const bf16x8 *>(sLo + offA + 32 * ks);
+                const bf16x8 bh = *reinterpret_cast<const bf16x8 *>(sHi + offB + 32 * ks);
+                const bf16x8 bl = *reinterpret_cast<const bf16x8 *>(sLo + offB + 32 * ks);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al, bh, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bl, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah, bh, acc, 0, 0, 0);
             }
         }
         // acc[v] = <X_i, X_j>, i = 16 I + 4 (lane / 16) + v, j = 16 J + lane % 16.
@@ -186,7 +202,7 @@ size_t interact_lds_bytes_per_sample(int T, int D)
 {
     const Geometry g = geometry(T, D);
     const int ldo = pad_up(D + T * (T + 1) / 2);
-    return g.x_floats * sizeof(float) + (size_t)ldo * 2;
+    return 2 * g.plane * sizeof(__bf16) + (size_t)ldo * 2;
 }
 
 hipError_t launch_interact(const float *x0, int ldx0, const float *pooled, int B, int T, int D,
@@ -194,7 +210,7 @@ hipError_t launch_interact(const float *x0, int ldx0, const float *pooled, int B
 {
     if (B <= 0) return hipSuccess;
     const Geometry g = geometry(T, D);
-    const size_t per = g.x_floats * sizeof(float) + (size_t)ldo * 2;
+    const size_t per = 2 * g.plane * sizeof(__bf16) + (size_t)ldo * 2;
     if (per > 64 * 1024) return hipErrorInvalidValue;  // rejected at model creation
     // Enough samples per block to give every wave about one tile; small blocks
     // (little LDS each) keep many of them resident, which hides the staging
@@ -204,11 +220,10 @@ hipError_t launch_interact(const float *x0, int ldx0, const float *pooled, int B
     const dim3 grid((B + spb - 1) / spb), block(IT_THREADS);
     __bf16 *o = static_cast<__bf16 *>(out_bf16);
     const size_t lds = spb * per;
-    switch (D) {
-    case 16: hipLaunchKernelGGL(interact_kernel<1>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
-    case 32: hipLaunchKernelGGL(interact_kernel<2>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
-    case 64: hipLaunchKernelGGL(interact_kernel<4>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
-    case 128: hipLaunchKernelGGL(interact_kernel<8>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
+    switch (g.ksteps) {
+    case 1: hipLaunchKernelGGL(interact_kernel<1>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
+    case 2: hipLaunchKernelGGL(interact_kernel<2>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
+    case 4: hipLaunchKernelGGL(interact_kernel<4>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
     default: hipLaunchKernelGGL(interact_kernel<0>, grid, block, lds, s, x0, ldx0, pooled, B, T, D, o, ldo, spb); break;
     }
     return hipGetLastError();

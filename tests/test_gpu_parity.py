@@ -231,7 +231,12 @@ def test_forward_every_stage_against_oracle(binding, T, R, D, dtype, B, F, hb, h
     P = m.debug_pooled().cpu().numpy().astype(np.float64)
     zo = orc.interact(x0, P)
     assert np.abs(z[:, :width] - zo).max() <= 2.0 ** -8 * np.abs(zo).max() + 1e-30
-    assert (np.abs(z[:, :width] - zo) <= 2.0 ** -8 * np.abs(zo) + 1e-6 * np.abs(zo).max()).all()
+    # per term: the bf16 narrowing of the output (2^-9 relative, 2^-8 allowed) plus the
+    # device's dot product, good to 2^-16 of sum |x_i y_i| (operands split into two
+    # bf16 halves on the matrix cores; 2^-14 allowed)
+    scale = orc.interact(np.abs(x0), np.abs(P))
+    scale[:, :D] = 0.0
+    assert (np.abs(z[:, :width] - zo) <= 2.0 ** -8 * np.abs(zo) + 2.0 ** -14 * scale + 1e-30).all()
     # logits
     H.check_logits(logits, exact["logits"], mirror["logits"])
     m.close()
