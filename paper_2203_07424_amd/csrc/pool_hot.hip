@@ -28,18 +28,26 @@ constexpr int PH_UNROLL = 4;    // cold row loads in flight per lane
 constexpr int PH_EMPTY = -1;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
+// One more row into the sums; a row that does not count is cleared as raw bits
+// first.  `one` is 1.0f held in a register: the product form lets each fp16
+// element be widened and added by a single mixed-precision fused multiply-add
+// (bit-identical to widening and adding, the product being exact).
 template <bool HALF>
-__device__ inline void add_row(float *acc, const f32x4 raw, bool ok)
+__device__ inline void add_row(float *acc, u32x4 raw, bool ok, float one)
 {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) raw[i] = ok ? raw[i] : 0u;
     if (HALF) {
         const f16x8 h = __builtin_bit_cast(f16x8, raw);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] += ok ? (float)h[i] : 0.0f;
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf((float)h[i], one, acc[i]);
     } else {
+        const f32x4 f = __builtin_bit_cast(f32x4, raw);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] += ok ? raw[i] : 0.0f;
+        for (int i = 0; i < 4; ++i) acc[i] += f[i];
     }
 }
 
@@ -54,8 +62,10 @@ template <int LPR, bool HALF>
 __global__ __launch_bounds__(PH_THREADS) void pool_hot_kernel(
     const TableDesc *__restrict__ tables, const int32_t *__restrict__ indices,
     const int32_t *__restrict__ offsets, float *__restrict__ pooled, int B, int T, int nbags,
-    int bags_per_block, int hcap, ErrRecord *err)
+    int bags_per_block, int hcap, float one, ErrRecord *err)
 {
+    typedef const __attribute__((address_space(1))) char *table_ptr;
+    typedef const __attribute__((address_space(1))) u32x4 *row_ptr;
     constexpr int RPW = 64 / LPR;
     constexpr int ROWBYTES = LPR * 16;
     constexpr int NACC = HALF ? 8 : 4;
@@ -115,7 +125,7 @@ __global__ __launch_bounds__(PH_THREADS) void pool_hot_kernel(
         __syncthreads();
 
         // ---- the bags of this pass, one per wave at a time
-        const char *lane_base = base + chunk * 16;
+        const table_ptr lane_base = (table_ptr)base + chunk * 16;
         for (long long bag = p0 + wave; bag < pend; bag += PH_WAVES) {
             const int b = (int)(bag - (long long)t * B);
             const int start = __builtin_amdgcn_readfirstlane(offsets[bag]);
@@ -166,7 +176,7 @@ __global__ __launch_bounds__(PH_THREADS) void pool_hot_kernel(
                 // cold rows: from memory, PH_UNROLL wave-wide loads in flight
                 const int csteps = (ncold + RPW - 1) / RPW;
                 for (int j = 0; j < csteps; j += PH_UNROLL) {
-                    f32x4 raw[PH_UNROLL];
+                    u32x4 raw[PH_UNROLL];
                     bool ok[PH_UNROLL];
 #pragma unroll
                     for (int u = 0; u < PH_UNROLL; ++u) {
@@ -174,10 +184,10 @@ __global__ __launch_bounds__(PH_THREADS) void pool_hot_kernel(
                         const int id = my_cold[p < PH_SEG ? p : PH_SEG - 1];
                         ok[u] = p < ncold;
                         const long long row = ok[u] ? id : 0;
-                        raw[u] = *reinterpret_cast<const f32x4 *>(lane_base + row * ROWBYTES);
+                        raw[u] = *(row_ptr)(lane_base + row * ROWBYTES);
                     }
 #pragma unroll
-                    for (int u = 0; u < PH_UNROLL; ++u) add_row<HALF>(acc, raw[u], ok[u]);
+                    for (int u = 0; u < PH_UNROLL; ++u) add_row<HALF>(acc, raw[u], ok[u], one);
                 }
                 // hot rows: from the LDS copy
                 const int hsteps = (nhot + RPW - 1) / RPW;
@@ -185,9 +195,9 @@ __global__ __launch_bounds__(PH_THREADS) void pool_hot_kernel(
                     const int p = j * RPW + sub;
                     const bool ok = p < nhot;
                     const int slot = ok ? my_hot[p < PH_SEG ? p : PH_SEG - 1] : 0;
-                    const f32x4 raw =
-                        *reinterpret_cast<const f32x4 *>(s_rows + (size_t)slot * ROWBYTES + chunk * 16);
-                    add_row<HALF>(acc, raw, ok);
+                    const u32x4 raw =
+                        *reinterpret_cast<const u32x4 *>(s_rows + (size_t)slot * ROWBYTES + chunk * 16);
+                    add_row<HALF>(acc, raw, ok, one);
                 }
                 __builtin_amdgcn_wave_barrier();
             }
@@ -238,10 +248,10 @@ hipError_t launch_lpr(bool half, const TableDesc *tables, int T, int B, const in
     const dim3 grid(blocks), block(PH_THREADS);
     if (half)
         hipLaunchKernelGGL((pool_hot_kernel<LPR, true>), grid, block, lds, s, tables, indices, offsets,
-                           pooled, B, T, nbags, bpb, hcap, err);
+                           pooled, B, T, nbags, bpb, hcap, 1.0f, err);
     else
         hipLaunchKernelGGL((pool_hot_kernel<LPR, false>), grid, block, lds, s, tables, indices, offsets,
-                           pooled, B, T, nbags, bpb, hcap, err);
+                           pooled, B, T, nbags, bpb, hcap, 1.0f, err);
     return hipGetLastError();
 }
 

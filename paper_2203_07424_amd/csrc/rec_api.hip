@@ -37,6 +37,7 @@ struct rec_model {
     int max_batch = 0;
     long long max_nnz = 0;
     std::vector<long long> rows;
+    long long max_rows = 0;  // of the largest table
     std::vector<Layer> bottom, top;
     std::vector<char> table_loaded;
     std::vector<TableDesc> desc;  // host copy of the device descriptors
@@ -155,6 +156,7 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     m->w0 = w0; m->z_width = (int)width;
     m->max_batch = cfg->max_batch; m->max_nnz = cfg->max_nnz;
     m->rows.assign(cfg->rows, cfg->rows + T);
+    for (int t = 0; t < T; ++t) m->max_rows = std::max<long long>(m->max_rows, cfg->rows[t]);
     m->table_loaded.assign(T, 0);
     m->desc.assign(T, TableDesc{nullptr, 0, nullptr, 0, 0});
     for (int t = 0; t < T; ++t) m->desc[t].rows = cfg->rows[t];
@@ -383,7 +385,7 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
             const PoolOut out = concat ? PoolOut{nullptr, act[0], m->z_ld, m->w0}
                                        : PoolOut{pooled, nullptr, 0, 0};
             REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
-                                out, nnz, m->stream_rows, err, s));
+                                out, nnz, m->stream_rows, m->max_rows, err, s));
         }
     }
     REC_MARK();

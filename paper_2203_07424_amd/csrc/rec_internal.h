@@ -54,9 +54,10 @@ struct PoolOut {
 // S1. Sum of the rows of every bag, fp32 accumulation.  nnz (the batch's id
 // count) only picks the launch shape: bags of a few ids share a wavefront.
 // stream_rows: load rows with the non-temporal hint (id streams without reuse).
+// max_rows: row count of the largest table (tables under 4 GiB take 32-bit offsets).
 hipError_t launch_pool(const TableDesc *tables, int dtype, int T, int D, int B,
                        const int32_t *indices, const int32_t *offsets, PoolOut out, long long nnz,
-                       bool stream_rows, ErrRecord *err, hipStream_t s);
+                       bool stream_rows, long long max_rows, ErrRecord *err, hipStream_t s);
 
 // S1 with the tables' hot rows served from an LDS copy (hcap: power of two >= the
 // longest hot list, pool_hot_fits(hcap, rowbytes) must hold).

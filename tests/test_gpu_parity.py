@@ -117,6 +117,79 @@ def test_streaming_row_loads_give_the_same_sums(binding):
         m.close()
 
 
+@pytest.mark.parametrize("hi,hot", [(150, False), (3, False), (150, True)])
+def test_slots_without_a_row_add_nothing_even_next_to_nan(binding, hi, hot):
+    # Lanes past the end of a bag and ids outside the table must not pick up any
+    # row: row 0, the nearest candidate, holds NaN and infinities here.
+    say("no-row slots", hi, hot)
+    g = np.random.default_rng(77 + hi)
+    for (T, R, D, dtype, B) in [(3, 900, 64, np.float16, 130), (2, 400, 32, np.float32, 67), (2, 300, 8, np.float16, 40)]:
+        tabs = [g.uniform(-0.05, 0.05, (R, D)).astype(dtype) for _ in range(T)]
+        for tab in tabs:
+            tab[0, ::3] = np.nan
+            tab[0, 1::3] = np.inf
+            tab[0, 2::3] = -np.inf
+        lens = g.integers(0, hi + 1, T * B).astype(np.int32)
+        idx = g.integers(1, R, int(lens.sum())).astype(np.int32)
+        bad_at = g.permutation(idx.size)[:7]
+        idx[bad_at] = np.array([R, -1, R + 5, -2 ** 31, 2 ** 31 - 1, R, -7], dtype=np.int32)
+        bottom, top = small_mlps(g, 4, D, T)
+        m = H.make_model(binding, tabs, bottom, top, B, idx.size, 4)
+        if hot:
+            for t in range(T):
+                m.load_hot_rows(t, g.integers(0, R, 64).astype(np.int32))
+        H.run(m, synth.Batch(g.standard_normal((B, 4)).astype(np.float32), idx, lens))
+        P, A, nbad, first = orc.pool(tabs, idx, lens, B, want_abs=True)
+        assert nbad == 7 and m.check() == (binding.REC_ERR_INDEX_RANGE, first)
+        got = m.debug_pooled().cpu().numpy()
+        assert np.isfinite(got).all()
+        H.check_pooled(got, P, A)
+        m.close()
+
+
+def test_table_beyond_four_gib(binding):
+    # Rows past byte 2^32 of a table: 64-bit row addresses, same sums.  The table
+    # is zero but for a few hundred rows, so the oracle works on those rows alone.
+    say("table > 4 GiB")
+    g = np.random.default_rng(91)
+    D, R, R2, B, F = 256, 4_400_000, 700, 90, 4          # 1 KiB rows: 4.5 GB
+    live = np.unique(np.concatenate([g.integers(1, R, 300), [1, 4194303, 4194304, 4194305, R - 1]]))
+    vals = g.uniform(-0.05, 0.05, (live.size, D)).astype(np.float32)
+    small = g.uniform(-0.05, 0.05, (R2, D)).astype(np.float32)
+    big = torch.zeros((R, D), dtype=torch.float32, device="cuda")
+    big[torch.from_numpy(live).cuda()] = torch.from_numpy(vals).cuda()
+    big[0] = float("nan")
+    lens = g.integers(0, 40, 2 * B).astype(np.int32)
+    n0 = int(lens[:B].sum())
+    pick = g.integers(0, live.size, n0)
+    idx = np.concatenate([live[pick], g.integers(0, R2, int(lens[B:].sum()))]).astype(np.int32)
+    compact = np.concatenate([pick, idx[n0:]]).astype(np.int32)   # the same bags on the compacted table
+    for pos, bad in [(3, R), (17, -1), (n0 - 1, 2 ** 31 - 1)]:
+        idx[pos] = bad
+        compact[pos] = -1
+    bottom, top = small_mlps(g, F, D, 2)
+    m = binding.RecModel(2, D, [R, R2], "f32", F, [F] + [W.shape[0] for W, _ in bottom],
+                         [top[0][0].shape[1]] + [W.shape[0] for W, _ in top], B, idx.size)
+    m.load_table(0, big)
+    m.load_table(1, torch.from_numpy(small).cuda())
+    H.load_mlps(binding, m, bottom, top)
+    batch = synth.Batch(g.standard_normal((B, F)).astype(np.float32), idx, lens)
+    for stream in (0, 1):
+        m.set_option(binding.REC_OPT_STREAM_ROWS, stream)
+        got_logits = H.run(m, batch)
+        assert m.check() == (binding.REC_ERR_INDEX_RANGE, 3)
+        P, A, nbad, first = orc.pool([vals, small], compact, lens, B, want_abs=True)
+        assert nbad == 3 and first == 3
+        got = m.debug_pooled().cpu().numpy()
+        assert np.isfinite(got).all()
+        H.check_pooled(got, P, A)
+        exact = orc.forward(batch.dense, [vals, small], compact, lens, bottom, top)
+        H.check_logits(got_logits, exact["logits"])
+    m.close()
+    del big
+    torch.cuda.empty_cache()
+
+
 def test_pooling_closed_forms_on_device(binding):
     say("pool closed forms")
     g = np.random.default_rng(7)
