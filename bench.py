@@ -110,6 +110,9 @@ def cpu_baseline(w, batches, bottom, top, n_samples: int) -> dict:
                       f"{dt:.2f} s wall on {threads} threads"}
 
 
+FUSE_MLP = "auto"   # --fuse-mlp: how runs of narrow FC layers are launched
+
+
 def build_model(binding, synth, torch, w, max_batch, share_tables=None):
     """Model of workload `w` with tables filled on the device (or shared with
     the model `share_tables`) and packed MLPs."""
@@ -134,6 +137,8 @@ def build_model(binding, synth, torch, w, max_batch, share_tables=None):
     for k, tower in enumerate(towers):
         for i, (W, b) in enumerate(tower):
             m.load_mlp(binding.REC_TOP + k, i, torch.from_numpy(W), torch.from_numpy(b))
+    if FUSE_MLP != "auto":
+        m.set_option(binding.REC_OPT_FUSE_MLP, 2 if FUSE_MLP == "on" else 0)
     torch.cuda.synchronize()
     # the oracle's pairwise-dot forward takes one stack, its tower forward a list of them
     return m, bottom, (towers if w.interaction == "concat" else towers[0])
@@ -330,6 +335,8 @@ def main() -> int:
     ap.add_argument("--stream-rows", choices=["auto", "on", "off"], default="auto",
                     help="pooling loads table rows with the non-temporal hint; auto = only for "
                          "workloads whose ids are drawn uniformly (no reuse for the caches to serve)")
+    ap.add_argument("--fuse-mlp", choices=["auto", "on", "off"], default="auto",
+                    help="runs of narrow FC layers as one kernel: the library's choice, always, never")
     ap.add_argument("--overlap", action="store_true",
                     help="run Bottom-FC on the library's side stream beside scan and pooling")
     ap.add_argument("--event-period", type=int, default=10,
@@ -349,6 +356,8 @@ def main() -> int:
     ap.add_argument("--sweep-iters", type=int, default=200)
     ap.add_argument("--sla-ms", type=float, default=20.0)
     args = ap.parse_args()
+    global FUSE_MLP
+    FUSE_MLP = args.fuse_mlp
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
         return 2

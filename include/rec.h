@@ -225,7 +225,15 @@ enum {
      * skewed (the "hot" entries of Sec. IV-A) and the caches then serve a large
      * share of the lookups (streaming is 20 % slower on Zipf(1.05) ids).  The
      * pooled sums are the same either way. */
-    REC_OPT_STREAM_ROWS = 1
+    REC_OPT_STREAM_ROWS = 1,
+    /* Consecutive FC layers of at most 1024 (padded) inputs and outputs can run
+     * as one kernel per stack, their activations held on chip between layers.
+     * 2: always; 0: never, every layer is a kernel of its own; 1 (default):
+     * where it was measured to pay, runs whose weights total at most 256 KiB
+     * (every block of such a kernel streams all weights of its run).  Same
+     * arithmetic either way: bf16 operands, fp32 accumulation, the one-output
+     * layer in fp32; sums are taken in a different order. */
+    REC_OPT_FUSE_MLP = 2
 };
 REC_API rec_status rec_set_option(rec_model *m, int32_t option, int32_t value);
 

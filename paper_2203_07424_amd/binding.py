@@ -32,6 +32,7 @@ REC_MAX_TOWERS = 8
 REC_DBG_OFFSETS, REC_DBG_POOLED, REC_DBG_BOTTOM_OUT, REC_DBG_INTERACT = 0, 1, 2, 3
 REC_OPT_OVERLAP_DENSE = 0
 REC_OPT_STREAM_ROWS = 1
+REC_OPT_FUSE_MLP = 2
 REC_NUM_STAGES = 6
 STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top_first", "top_rest")
 

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "librec_mi355x.so")
 
-SOURCES = ["scan.hip", "pool.hip", "pool_hot.hip", "gemm.hip", "gemm_big.hip", "interact.hip", "synth_fill.hip", "rec_api.hip"]
+SOURCES = ["scan.hip", "pool.hip", "pool_hot.hip", "gemm.hip", "gemm_big.hip", "mlp_chain.hip", "interact.hip", "synth_fill.hip", "rec_api.hip"]
 
 # The packed-fp32 target feature is switched off for all device code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -22,8 +22,11 @@ struct Layer {
     const void *W = nullptr;      // bf16 [Npad][Kpad]; fp32 [Kpad] for the one-output layer
     const float *bias = nullptr;  // fp32 [Npad]
     bool dot = false;             // last Predict-FC layer: fp32 dot product, not a GEMM
+    bool chain = false;           // narrow enough for the kernel that runs several layers on chip
+    const void *Wc = nullptr;     // chain layers: the same weights in MFMA fragment order
     bool loaded = false;
     size_t w_bytes() const { return dot ? sizeof(float) * Kpad : 2 * (size_t)Npad * Kpad; }
+    size_t chain_bytes() const { return chain ? 2 * (size_t)Npad * Kpad : 0; }
 };
 
 }  // namespace
@@ -55,6 +58,7 @@ struct rec_model {
     // Bottom-FC runs on a stream of the library's own, beside scan and pooling.
     bool overlap_dense = false;
     bool stream_rows = false;  // pooling loads rows with the non-temporal hint
+    int fuse_mlp = 1;          // runs of narrow layers through the on-chip chain kernel: 0 never, 1 where it pays, 2 always
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
@@ -168,6 +172,7 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
         for (int i = 0; i < n; ++i) {
             v[i].K = w[i]; v[i].N = w[i + 1];
             v[i].Kpad = pad_up(w[i]); v[i].Npad = pad_up(w[i + 1]);
+            v[i].chain = chain_layer_fits(v[i].Kpad, v[i].Npad);
             if (i + 1 < n || side_by_side == 1)  // the one-output layer leaves no activation row
                 m->act_ld = std::max(m->act_ld, side_by_side * v[i].Npad);
         }
@@ -178,6 +183,7 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     for (int k = 0; k < towers; ++k) {
         fill(&m->top[(size_t)k * cfg->n_top], cfg->top_widths, cfg->n_top, towers);
         m->top[(size_t)k * cfg->n_top + cfg->n_top - 1].dot = true;
+        m->top[(size_t)k * cfg->n_top + cfg->n_top - 1].chain = false;
     }
     m->act_row_bytes = 2 * (size_t)m->act_ld;
     if (cfg->n_top > 1)  // the layer feeding the dot leaves fp32
@@ -225,7 +231,7 @@ rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *s
             hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess)
             return REC_ERR_DEVICE;
     }
-    if (fc_big_prepare() != hipSuccess) return REC_ERR_DEVICE;
+    if (fc_big_prepare() != hipSuccess || chain_prepare() != hipSuccess) return REC_ERR_DEVICE;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
@@ -275,7 +281,7 @@ size_t rec_mlp_packed_bytes(const rec_model *m, int32_t which, int32_t layer)
     if (!m) return 0;
     const Layer *l = find_layer(const_cast<rec_model *>(m), which, layer);
     if (!l) return 0;
-    return align_up(l->w_bytes()) + align_up(sizeof(float) * l->Npad);
+    return align_up(l->w_bytes()) + align_up(sizeof(float) * l->Npad) + align_up(l->chain_bytes());
 }
 
 rec_status rec_load_mlp(rec_model *m, int32_t which, int32_t layer, const float *dev_W,
@@ -291,6 +297,11 @@ rec_status rec_load_mlp(rec_model *m, int32_t which, int32_t layer, const float 
     const hipError_t e = l->dot ? launch_pack_dot(dev_W, dev_b, l->K, l->Kpad, reinterpret_cast<float *>(p), bias, s)
                                 : launch_pack_fc(dev_W, dev_b, l->N, l->K, l->Npad, l->Kpad, p, bias, s);
     if (e != hipSuccess) return REC_ERR_DEVICE;
+    if (l->chain) {
+        char *pc = p + align_up(l->w_bytes()) + align_up(sizeof(float) * l->Npad);
+        if (launch_pack_chain(dev_W, l->N, l->K, l->Npad, l->Kpad, pc, s) != hipSuccess) return REC_ERR_DEVICE;
+        l->Wc = pc;
+    }
     l->W = p;
     l->bias = bias;
     l->loaded = true;
@@ -337,22 +348,70 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
     // stream, forked from and joined back into the caller's stream.
     const bool overlap = m->overlap_dense && !m->bottom.empty();
     hipStream_t sd = overlap ? m->side : s;
+    // A run of chain layers [i, j) of one or several stacks side by side, layer l of
+    // stack k being layers[k * per_stack + l].
+    auto chain_run = [&](const Layer *layers, int per_stack, int G, int i, int j, ChainProblem &c) {
+        c.n_layers = j - i;
+        c.groups = G;
+        c.K = layers[i].K;
+        for (int l = i; l < j; ++l) {
+            c.Kpad[l - i] = layers[l].Kpad;
+            c.Npad[l - i] = layers[l].Npad;
+            c.relu[l - i] = 1;
+            for (int k = 0; k < G; ++k) {
+                c.W[l - i][k] = layers[(size_t)k * per_stack + l].Wc;
+                c.bias[l - i][k] = layers[(size_t)k * per_stack + l].bias;
+            }
+        }
+    };
+    // How far a chain that starts at layer i of n reaches (i: no chain here).  Every
+    // block of a chain streams all weights of its run, which costs more than the
+    // launches it saves once they no longer are a small fraction of a block's L1
+    // bandwidth over a launch time: left to itself (fuse_mlp == 1) the library
+    // chains runs of up to CHAIN_AUTO_BYTES of weights.
+    constexpr size_t CHAIN_AUTO_BYTES = 256 * 1024;
+    auto chain_end = [&](const Layer *layers, int i, int n) {
+        if (m->fuse_mlp == 0) return i;
+        int j = i;
+        size_t bytes = 0;
+        while (j < n && layers[j].chain && j - i < CHAIN_MAX_LAYERS) bytes += layers[j++].chain_bytes();
+        return m->fuse_mlp == 1 && bytes > CHAIN_AUTO_BYTES ? i : j;
+    };
     auto bottom_fc = [&]() -> hipError_t {
         // ReLU after every layer; the last one leaves fp32 for the interaction.
-        FcProblem p{};
-        p.A = dev_dense; p.a_f32 = true; p.lda = m->F;
-        p.M = B; p.relu = true; p.groups = 1; p.num_cus = m->num_cus;
-        for (size_t i = 0; i < m->bottom.size(); ++i) {
-            const Layer &l = m->bottom[i];
-            const bool last = i + 1 == m->bottom.size();
-            p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
-            p.g.W[0] = l.W; p.g.bias[0] = l.bias;
-            p.C = last ? static_cast<void *>(m->at<float>(m->off_x0)) : act[1 + (i & 1)];
-            p.out_f32 = last;
-            p.ldc = last ? m->x0_ld : m->act_ld;
-            const hipError_t e = launch_fc(p, sd);
+        const int n = (int)m->bottom.size();
+        const Layer *layers = m->bottom.data();
+        const void *A = dev_dense;
+        bool a_f32 = true;
+        int lda = m->F, launches = 0;
+        for (int i = 0; i < n;) {
+            const int j = chain_end(layers, i, n);
+            const int upto = j > i ? j : i + 1;
+            const bool last = upto == n;
+            void *C = last ? static_cast<void *>(m->at<float>(m->off_x0)) : act[1 + (launches & 1)];
+            const int ldc = last ? m->x0_ld : m->act_ld;
+            hipError_t e;
+            if (j > i) {
+                ChainProblem c{};
+                c.A = A; c.a_f32 = a_f32; c.lda = lda; c.a_stride = 0; c.M = B;
+                chain_run(layers, n, 1, i, j, c);
+                c.out_mode = last ? CHAIN_OUT_F32 : CHAIN_OUT_BF16;
+                c.C = C; c.ldc = ldc; c.c_stride = 0;
+                e = launch_mlp_chain(c, sd);
+            } else {
+                const Layer &l = layers[i];
+                FcProblem p{};
+                p.A = A; p.a_f32 = a_f32; p.lda = lda;
+                p.M = B; p.relu = true; p.groups = 1; p.num_cus = m->num_cus;
+                p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
+                p.g.W[0] = l.W; p.g.bias[0] = l.bias;
+                p.C = C; p.out_f32 = last; p.ldc = ldc;
+                e = launch_fc(p, sd);
+            }
             if (e != hipSuccess) return e;
-            p.A = p.C; p.lda = p.ldc; p.a_f32 = false;
+            A = C; lda = ldc; a_f32 = false;
+            ++launches;
+            i = upto;
         }
         return hipSuccess;
     };
@@ -417,26 +476,50 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
             p.g.dot_bias[k] = dotl.bias;
         }
         bool cur_f32 = false, done = false, first_marked = false;
-        for (int i = 0; i + 1 < n_top && !done; ++i) {
-            const Layer &l = m->top[i];  // shape of layer i in every tower
-            for (int k = 0; k < G; ++k) {
-                p.g.W[k] = m->top[(size_t)k * n_top + i].W;
-                p.g.bias[k] = m->top[(size_t)k * n_top + i].bias;
-            }
-            p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
-            const bool feeds_dot = i + 2 == n_top;
-            if (feeds_dot && fc_can_fuse_dot(l.Npad)) {
-                p.C = nullptr; p.out_f32 = false; p.ldc = 0; p.c_stride = 0;
-                p.dot_out = dev_logits; p.dot_ld = G;
-                REC_TRY(launch_fc(p, s));
-                done = true;
+        const Layer *layers = m->top.data();
+        const int n = n_top - 1;  // layers ahead of the one-output layer
+        int launches = 0;
+        for (int i = 0; i < n && !done;) {
+            const Layer &l = layers[i];  // shape of layer i in every tower
+            const int j = chain_end(layers, i, n);
+            if (j > i) {
+                ChainProblem c{};
+                c.A = p.A; c.a_f32 = false; c.lda = p.lda; c.a_stride = p.a_stride; c.M = B;
+                chain_run(layers, n_top, G, i, j, c);
+                if (j == n) {
+                    c.out_mode = CHAIN_OUT_DOT;
+                    for (int k = 0; k < G; ++k) { c.dot_w[k] = p.g.dot_w[k]; c.dot_bias[k] = p.g.dot_bias[k]; }
+                    c.dot_out = dev_logits; c.dot_ld = G;
+                    done = true;
+                } else {
+                    c.out_mode = CHAIN_OUT_BF16;
+                    c.C = act[1 + (launches & 1)]; c.ldc = G * layers[j - 1].Npad; c.c_stride = layers[j - 1].Npad;
+                    p.A = c.C; p.lda = c.ldc; p.a_stride = c.c_stride; p.a_f32 = false;
+                }
+                REC_TRY(launch_mlp_chain(c, s));
+                i = j;
             } else {
-                p.C = act[1 + (i & 1)]; p.out_f32 = feeds_dot; p.ldc = G * l.Npad; p.c_stride = l.Npad;
-                REC_TRY(launch_fc(p, s));
-                p.A = p.C; p.lda = p.ldc; p.a_stride = p.c_stride; p.a_f32 = false;
-                cur_f32 = feeds_dot;
+                for (int k = 0; k < G; ++k) {
+                    p.g.W[k] = m->top[(size_t)k * n_top + i].W;
+                    p.g.bias[k] = m->top[(size_t)k * n_top + i].bias;
+                }
+                p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
+                const bool feeds_dot = i + 1 == n;
+                if (feeds_dot && fc_can_fuse_dot(l.Npad)) {
+                    p.C = nullptr; p.out_f32 = false; p.ldc = 0; p.c_stride = 0;
+                    p.dot_out = dev_logits; p.dot_ld = G;
+                    REC_TRY(launch_fc(p, s));
+                    done = true;
+                } else {
+                    p.C = act[1 + (launches & 1)]; p.out_f32 = feeds_dot; p.ldc = G * l.Npad; p.c_stride = l.Npad;
+                    REC_TRY(launch_fc(p, s));
+                    p.A = p.C; p.lda = p.ldc; p.a_stride = p.c_stride; p.a_f32 = false;
+                    cur_f32 = feeds_dot;
+                }
+                ++i;
             }
-            if (i == 0) {  // the first (widest) layer is timed on its own
+            ++launches;
+            if (!first_marked) {  // the first launch (the widest layer, or the run it starts) is timed on its own
                 REC_MARK();
                 first_marked = true;
             }
@@ -500,6 +583,10 @@ rec_status rec_set_option(rec_model *m, int32_t option, int32_t value)
     switch (option) {
     case REC_OPT_OVERLAP_DENSE: m->overlap_dense = value != 0; return REC_OK;
     case REC_OPT_STREAM_ROWS: m->stream_rows = value != 0; return REC_OK;
+    case REC_OPT_FUSE_MLP:
+        if (value < 0 || value > 2) return REC_ERR_ARG;
+        m->fuse_mlp = value;
+        return REC_OK;
     default: return REC_ERR_ARG;
     }
 }

@@ -104,6 +104,39 @@ hipError_t launch_fc_big(const FcProblem &p, int num_cus, hipStream_t s);
 // capture): lets these kernels use their more-than-64-KB LDS tiles.
 hipError_t fc_big_prepare();
 
+// A run of layers of every stack in one launch, activations kept on chip:
+//   X_0 = A_g (bf16 [M][lda], or fp32 with a_f32; columns >= K read as zero),
+//   X_{L+1} = act_L(X_L W_{L,g}^T + bias_{L,g}),  act_L = ReLU where relu[L] != 0,
+// each layer narrowing its input to bf16 as the per-layer path does.  Layer L is
+// Kpad[L] -> Npad[L] with Kpad[L + 1] == Npad[L], all at most CHAIN_MAX_WIDTH
+// and multiples of PAD; W[L][g] is the fragment order launch_pack_chain() writes.
+// The last X goes to C_g = C + g * c_stride (CHAIN_OUT_BF16 / CHAIN_OUT_F32, row
+// stride ldc), or (CHAIN_OUT_DOT) into the one-output layer that follows:
+//   dot_out[m * dot_ld + g] = sum_n X[m][n] * dot_w[g][n] + dot_bias[g][0]   in fp32.
+constexpr int CHAIN_MAX_LAYERS = 6;
+constexpr int CHAIN_MAX_WIDTH = 1024;
+enum { CHAIN_OUT_BF16 = 0, CHAIN_OUT_F32 = 1, CHAIN_OUT_DOT = 2 };
+struct ChainProblem {
+    const void *A; bool a_f32; int lda; long long a_stride;
+    int M, K;
+    int n_layers, groups;
+    int Kpad[CHAIN_MAX_LAYERS], Npad[CHAIN_MAX_LAYERS], relu[CHAIN_MAX_LAYERS];
+    const void *W[CHAIN_MAX_LAYERS][MAX_GROUPS];
+    const float *bias[CHAIN_MAX_LAYERS][MAX_GROUPS];
+    int out_mode;
+    void *C; int ldc; long long c_stride;
+    const float *dot_w[MAX_GROUPS];
+    const float *dot_bias[MAX_GROUPS];
+    float *dot_out; int dot_ld;
+    int ld_lds, a_vec;  // filled in by launch_mlp_chain()
+};
+bool chain_layer_fits(int Kpad, int Npad);
+hipError_t launch_mlp_chain(const ChainProblem &p, hipStream_t s);
+// Once per process and device, before the first launch (not under stream capture).
+hipError_t chain_prepare();
+// fp32 [N][K] -> bf16 [Npad * Kpad] in MFMA fragment order (nearest even, zero padded).
+hipError_t launch_pack_chain(const float *W, int N, int K, int Npad, int Kpad, void *W_packed, hipStream_t s);
+
 // Last Predict-FC layer of every stack: logits[m * ld + g] = sum_k A_g[m][k] * w_g[k] + bias_g[0]
 // in fp32.  A_g = A + g * a_stride is fp32 [M][lda] (a_f32) or bf16 [M][lda];
 // w_g = groups.dot_w[g] is fp32 [Kpad], zero padded, bias_g = groups.dot_bias[g].

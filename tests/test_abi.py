@@ -121,6 +121,8 @@ def test_null_and_order_errors_without_device(binding):
     assert b.rec_stage_ms(h)[0] == b.REC_ERR_STATE
     assert b.rec_set_profiling(h, 4, 0) == b.REC_ERR_ARG
     assert b.rec_set_option(h, 99, 1) == b.REC_ERR_ARG
+    assert b.rec_set_option(h, b.REC_OPT_FUSE_MLP, 3) == b.REC_ERR_ARG
+    assert b.rec_set_option(h, b.REC_OPT_FUSE_MLP, 2) == b.REC_OK
     lib.rec_bind_workspace.restype = C.c_int
     lib.rec_bind_workspace.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     assert lib.rec_bind_workspace(h, None, 1 << 20, None) == b.REC_ERR_ARG
