@@ -229,8 +229,9 @@ enum {
     /* Consecutive FC layers of at most 1024 (padded) inputs and outputs can run
      * as one kernel per stack, their activations held on chip between layers.
      * 2: always; 0: never, every layer is a kernel of its own; 1 (default):
-     * where it was measured to pay, runs whose weights total at most 256 KiB
-     * (every block of such a kernel streams all weights of its run).  Same
+     * where it was measured to pay, runs that save at least one launch and
+     * whose weights total at most 256 KiB (every block of such a kernel
+     * streams all weights of its run).  Same
      * arithmetic either way: bf16 operands, fp32 accumulation, the one-output
      * layer in fp32; sums are taken in a different order. */
     REC_OPT_FUSE_MLP = 2

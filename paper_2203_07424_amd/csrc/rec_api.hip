@@ -368,14 +368,17 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
     // block of a chain streams all weights of its run, which costs more than the
     // launches it saves once they no longer are a small fraction of a block's L1
     // bandwidth over a launch time: left to itself (fuse_mlp == 1) the library
-    // chains runs of up to CHAIN_AUTO_BYTES of weights.
+    // chains runs of up to CHAIN_AUTO_BYTES of weights, and only where that saves
+    // a launch (dot_after: the one-output layer follows layer n - 1).
     constexpr size_t CHAIN_AUTO_BYTES = 256 * 1024;
-    auto chain_end = [&](const Layer *layers, int i, int n) {
+    auto chain_end = [&](const Layer *layers, int i, int n, bool dot_after) {
         if (m->fuse_mlp == 0) return i;
         int j = i;
         size_t bytes = 0;
         while (j < n && layers[j].chain && j - i < CHAIN_MAX_LAYERS) bytes += layers[j++].chain_bytes();
-        return m->fuse_mlp == 1 && bytes > CHAIN_AUTO_BYTES ? i : j;
+        if (m->fuse_mlp == 2 || j == i) return j;
+        const int saved = (j - i - 1) + (dot_after && j == n && !fc_can_fuse_dot(layers[j - 1].Npad) ? 1 : 0);
+        return bytes > CHAIN_AUTO_BYTES || saved < 1 ? i : j;
     };
     auto bottom_fc = [&]() -> hipError_t {
         // ReLU after every layer; the last one leaves fp32 for the interaction.
@@ -385,7 +388,7 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         bool a_f32 = true;
         int lda = m->F, launches = 0;
         for (int i = 0; i < n;) {
-            const int j = chain_end(layers, i, n);
+            const int j = chain_end(layers, i, n, false);
             const int upto = j > i ? j : i + 1;
             const bool last = upto == n;
             void *C = last ? static_cast<void *>(m->at<float>(m->off_x0)) : act[1 + (launches & 1)];
@@ -481,7 +484,7 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         int launches = 0;
         for (int i = 0; i < n && !done;) {
             const Layer &l = layers[i];  // shape of layer i in every tower
-            const int j = chain_end(layers, i, n);
+            const int j = chain_end(layers, i, n, true);
             if (j > i) {
                 ChainProblem c{};
                 c.A = p.A; c.a_f32 = false; c.lda = p.lda; c.a_stride = p.a_stride; c.M = B;
