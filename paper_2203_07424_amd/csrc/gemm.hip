@@ -151,46 +151,44 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
         }                                                                                   \
     } while (0)
 
-#pragma unroll
-    for (int p = 0; p < P; ++p)
-        if (p < nk) REC_FC_FETCH(p, p);
+    // One k-tile out of register slot u: into LDS, multiply; the slot is refilled
+    // with tile kt + P.  Fetches past the last tile repeat it instead of being
+    // skipped: with a branch around them the compiler can no longer count the
+    // loads in flight and waits for all of them before every LDS write.
+#define REC_FC_TILE(kt, u)                                                                  \
+    do {                                                                                    \
+        __syncthreads();                                                                    \
+        _Pragma("unroll") for (int i = 0; i < A_LOADS; ++i)                                 \
+            *reinterpret_cast<bf16x8 *>(&sA[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = ra[u][i].narrow(); \
+        _Pragma("unroll") for (int i = 0; i < W_LOADS; ++i)                                 \
+            *reinterpret_cast<bf16x8 *>(&sW[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = rw[u][i]; \
+        __syncthreads();                                                                    \
+        REC_FC_FETCH(min((kt) + P, nk - 1), u);                                             \
+        _Pragma("unroll") for (int kk = 0; kk < BK / 16; ++kk) {                            \
+            const int kofs = kk * 16 + (lane >> 5) * 8;                                     \
+            bf16x8 fw[TN], fa[TM];                                                          \
+            _Pragma("unroll") for (int i = 0; i < TN; ++i)                                  \
+                fw[i] = *reinterpret_cast<const bf16x8 *>(&sW[(wn * WN + i * 32 + (lane & 31)) * LDS_LD + kofs]); \
+            _Pragma("unroll") for (int j = 0; j < TM; ++j)                                  \
+                fa[j] = *reinterpret_cast<const bf16x8 *>(&sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]); \
+            _Pragma("unroll") for (int i = 0; i < TN; ++i)                                  \
+                _Pragma("unroll") for (int j = 0; j < TM; ++j)                              \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0); \
+        }                                                                                   \
+    } while (0)
 
-    for (int kt0 = 0; kt0 < nk; kt0 += P) {
 #pragma unroll
-        for (int u = 0; u < P; ++u) {
-            const int kt = kt0 + u;
-            if (kt < nk) {
-                __syncthreads();
+    for (int p = 0; p < P; ++p) REC_FC_FETCH(min(p, nk - 1), p);
+
+    int kt0 = 0;
+    for (; kt0 + P <= nk; kt0 += P) {
 #pragma unroll
-                for (int i = 0; i < A_LOADS; ++i)
-                    *reinterpret_cast<bf16x8 *>(&sA[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) =
-                        ra[u][i].narrow();
-#pragma unroll
-                for (int i = 0; i < W_LOADS; ++i)
-                    *reinterpret_cast<bf16x8 *>(&sW[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = rw[u][i];
-                __syncthreads();
-                if (kt + P < nk) REC_FC_FETCH(kt + P, u);
-#pragma unroll
-                for (int kk = 0; kk < BK / 16; ++kk) {
-                    const int kofs = kk * 16 + (lane >> 5) * 8;
-                    bf16x8 fw[TN], fa[TM];
-#pragma unroll
-                    for (int i = 0; i < TN; ++i)
-                        fw[i] = *reinterpret_cast<const bf16x8 *>(
-                            &sW[(wn * WN + i * 32 + (lane & 31)) * LDS_LD + kofs]);
-#pragma unroll
-                    for (int j = 0; j < TM; ++j)
-                        fa[j] = *reinterpret_cast<const bf16x8 *>(
-                            &sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]);
-#pragma unroll
-                    for (int i = 0; i < TN; ++i)
-#pragma unroll
-                        for (int j = 0; j < TM; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
-                }
-            }
-        }
+        for (int u = 0; u < P; ++u) REC_FC_TILE(kt0 + u, u);
     }
+#pragma unroll
+    for (int u = 0; u < P - 1; ++u)
+        if (kt0 + u < nk) REC_FC_TILE(kt0 + u, u);
+#undef REC_FC_TILE
 #undef REC_FC_FETCH
 
     // acc[i][j][r]: feature n = 8 * (r / 4) + 4 * (lane / 32) + r % 4, sample m = lane % 32.

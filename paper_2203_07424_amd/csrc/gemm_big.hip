@@ -171,6 +171,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void fc_big_kernel(
                 fa[j] = *reinterpret_cast<const bf16x8 *>(&sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]); \
             if (STASH) REC_BIG_STASH_PART((kt) + 1, cur_ ^ 1, kk);                                   \
             if (FETCH) REC_BIG_FETCH_PART((kt) + 2, kk);                                   \
+            __builtin_amdgcn_sched_barrier(0); /* else the compiler sinks all fetches to the end of the k-tile */ \
             _Pragma("unroll") for (int i = 0; i < TN; ++i)                                 \
                 _Pragma("unroll") for (int j = 0; j < TM; ++j)                             \
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0); \
