@@ -164,17 +164,20 @@ __global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__
             *reinterpret_cast<bf16x8 *>(&sW[(ld_row + 32 * i) * LDS_LD + ld_chunk * 8]) = rw[u][i]; \
         __syncthreads();                                                                    \
         REC_FC_FETCH(min((kt) + P, nk - 1), u);                                             \
+        /* all operand fragments of the k-tile are requested before the first product: */   \
+        /* read-wait-multiply per 16 k would expose the LDS latency four times */          \
+        bf16x8 fw[BK / 16][TN], fa[BK / 16][TM];                                            \
         _Pragma("unroll") for (int kk = 0; kk < BK / 16; ++kk) {                            \
             const int kofs = kk * 16 + (lane >> 5) * 8;                                     \
-            bf16x8 fw[TN], fa[TM];                                                          \
             _Pragma("unroll") for (int i = 0; i < TN; ++i)                                  \
-                fw[i] = *reinterpret_cast<const bf16x8 *>(&sW[(wn * WN + i * 32 + (lane & 31)) * LDS_LD + kofs]); \
+                fw[kk][i] = *reinterpret_cast<const bf16x8 *>(&sW[(wn * WN + i * 32 + (lane & 31)) * LDS_LD + kofs]); \
             _Pragma("unroll") for (int j = 0; j < TM; ++j)                                  \
-                fa[j] = *reinterpret_cast<const bf16x8 *>(&sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]); \
+                fa[kk][j] = *reinterpret_cast<const bf16x8 *>(&sA[(wm * WM + j * 32 + (lane & 31)) * LDS_LD + kofs]); \
+        }                                                                                   \
+        _Pragma("unroll") for (int kk = 0; kk < BK / 16; ++kk)                              \
             _Pragma("unroll") for (int i = 0; i < TN; ++i)                                  \
                 _Pragma("unroll") for (int j = 0; j < TM; ++j)                              \
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0); \
-        }                                                                                   \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[kk][i], fa[kk][j], acc[i][j], 0, 0, 0); \
     } while (0)
 
 #pragma unroll

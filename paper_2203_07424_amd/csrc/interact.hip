@@ -80,34 +80,45 @@ __global__ __launch_bounds__(IT_THREADS) void interact_kernel(const float *__res
     // are issued IT_BATCH at a time before their LDS stores.
     const int c4n = g.dp / 4;             // 4-column groups per (padded) row
     const int n4 = g.Vpad * c4n;          // ... per sample
+    // Item f = tid + k * IT_THREADS is row f / c4n, group f % c4n: divided once per
+    // thread, then stepped (a division by a run-time value costs some 20 vector
+    // instructions, and this kernel is bound by instruction issue).
+    const int step_row = IT_THREADS / c4n, step_c4 = IT_THREADS % c4n;  // wave-uniform
+    const int row_first = tid / c4n, c4_first = tid - row_first * c4n;
     for (int s = 0; s < ns; ++s) {
         const long long b = b0 + s;
         const float *px0 = x0 + b * ldx0;
         const float *pp = pooled + b * T * D - D;  // row r >= 1 sits at pp + r * D
         __bf16 *hi = sHi + s * g.plane, *lo = sLo + s * g.plane;
+        int row_next = row_first, c4_next = c4_first;
         for (int f0 = tid; f0 < n4; f0 += IT_BATCH * IT_THREADS) {
             f32x4 v[IT_BATCH];
+            int row[IT_BATCH], c4[IT_BATCH];
 #pragma unroll
             for (int u = 0; u < IT_BATCH; ++u) {
-                const int f = f0 + u * IT_THREADS;
-                const int row = f / c4n, c4 = f - row * c4n;
+                row[u] = row_next;
+                c4[u] = c4_next;
+                c4_next += step_c4;
+                row_next += step_row;
+                if (c4_next >= c4n) {
+                    c4_next -= c4n;
+                    ++row_next;
+                }
                 v[u] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-                if (f < n4 && row < g.V && c4 < g.d4)
-                    v[u] = *reinterpret_cast<const f32x4 *>((row == 0 ? px0 : pp + (size_t)row * D) + 4 * c4);
+                if (row[u] < g.V && c4[u] < g.d4)  // rows past Vpad (items f >= n4) are past V too
+                    v[u] = *reinterpret_cast<const f32x4 *>((row[u] == 0 ? px0 : pp + (size_t)row[u] * D) + 4 * c4[u]);
             }
 #pragma unroll
             for (int u = 0; u < IT_BATCH; ++u) {
-                const int f = f0 + u * IT_THREADS;
-                const int row = f / c4n, c4 = f - row * c4n;
-                if (f < n4) {
+                if (f0 + u * IT_THREADS < n4) {
                     bf16x4 h, l;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         h[i] = (__bf16)v[u][i];
                         l[i] = (__bf16)(v[u][i] - (float)h[i]);
                     }
-                    *reinterpret_cast<bf16x4 *>(hi + (size_t)row * g.ld + 4 * c4) = h;
-                    *reinterpret_cast<bf16x4 *>(lo + (size_t)row * g.ld + 4 * c4) = l;
+                    *reinterpret_cast<bf16x4 *>(hi + (size_t)row[u] * g.ld + 4 * c4[u]) = h;
+                    *reinterpret_cast<bf16x4 *>(lo + (size_t)row[u] * g.ld + 4 * c4[u]) = l;
                 }
             }
         }
