@@ -177,3 +177,27 @@ def test_chain_in_a_graph_and_beside_pooling(binding):
     exact = orc.forward(dense, tabs, idx, lens, bottom, top)
     H.check_logits(eager, exact["logits"], mirror["logits"])
     m.close()
+
+
+@pytest.mark.parametrize("name", ["rmc2", "rmc1", "mtwnd"])
+def test_full_size_workload_with_every_possible_chain(binding, name):
+    """The named workload at full size with chains forced wherever the layer
+    shapes allow (by itself the library chains only the narrow stacks); the
+    oracle recomputes a spread of samples."""
+    w = synth.WORKLOADS[name]
+    say("full-size workload, chains forced", name)
+    m, bottom, top = H.make_workload_model(binding, w)
+    m.set_option(binding.REC_OPT_FUSE_MLP, 2)
+    batch = synth.draw_batch(w, 0)
+    forced = H.run(m, batch)
+    assert m.check() == (binding.REC_OK, -1)
+    m.set_option(binding.REC_OPT_FUSE_MLP, 0)
+    plain = H.run(m, batch)
+    g = np.random.default_rng(6)
+    pick = np.unique(np.concatenate([[0, 1, 31, 32, w.batch - 33, w.batch - 1], g.integers(0, w.batch, 40)]))
+    exact = H.oracle_on_slice(w, batch, pick, bottom, top)
+    mirror = H.oracle_on_slice(w, batch, pick, bottom, top, orc.BF16_MIRROR)
+    check(forced[pick], exact["logits"], mirror["logits"], plain[pick])
+    assert np.isfinite(forced).all()
+    m.close()
+    torch.cuda.empty_cache()
