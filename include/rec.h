@@ -198,14 +198,16 @@ REC_API rec_status rec_forward(rec_model *m, const float *dev_dense, const int32
                        const int32_t *dev_lengths, int32_t batch, int64_t nnz,
                        float *dev_logits, void *stream);
 
-/* Waits for `stream`, reads and clears the device error record.  Returns REC_OK,
+/* Waits for `stream` (and, pipelined, for the outstanding dense stages), reads
+ * and clears the device error record.  Returns REC_OK,
  * REC_ERR_LENGTHS (first_bad_pos = position in lengths of the first negative
  * one, or -1 when only the total disagreed with nnz) or REC_ERR_INDEX_RANGE
  * (first_bad_pos = smallest position in indices of an id outside its table).
  * Length faults win over index faults.  first_bad_pos may be null. */
 REC_API rec_status rec_check(rec_model *m, void *stream, int64_t *first_bad_pos);
 
-/* Device pointer of an intermediate buffer of the last forward (REC_DBG_*).
+/* Device pointer of an intermediate buffer of the last forward (REC_DBG_*);
+ * pipelined models: of the last call's frame, valid once its dense stages are done.
  * ld_out (may be null) receives the row stride in elements where it applies. */
 REC_API rec_status rec_debug_get(rec_model *m, int32_t what, const void **dev_ptr, int64_t *ld_out);
 
@@ -234,9 +236,39 @@ enum {
      * streams all weights of its run).  Same
      * arithmetic either way: bf16 operands, fp32 accumulation, the one-output
      * layer in fp32; sums are taken in a different order. */
-    REC_OPT_FUSE_MLP = 2
+    REC_OPT_FUSE_MLP = 2,
+    /* 1: sparse-dense pipeline across batches (Sec. IV-A, "S-D pipeline": the
+     * SparseNet of one query runs beside the DenseNet of another; Predict-FC
+     * waits for both, Sec. III-A).  rec_forward() then enqueues the offsets
+     * scan and the pooling on the caller's stream and Bottom-FC, interaction
+     * and Predict-FC on a second stream (rec_set_dense_stream(), else one of
+     * the library's own), ordered by events, so that the dense stages of batch
+     * i run while batch i + 1 is pooled.  The workspace holds two copies of
+     * the per-batch buffers, so the option is set before rec_workspace_bytes()
+     * and rec_bind_workspace() (REC_ERR_STATE once a workspace is bound).
+     * What changes for the caller: the logits of a call, and the caller's
+     * right to reuse that call's input buffers, are ordered on `stream` only
+     * behind the NEXT rec_forward() on it, or behind rec_drain(); all calls of
+     * one model go to one stream.  Same kernels, same results.  0 (default):
+     * everything in order on the caller's stream. */
+    REC_OPT_PIPELINE = 3
 };
 REC_API rec_status rec_set_option(rec_model *m, int32_t option, int32_t value);
+
+/* The stream on which a pipelined model (REC_OPT_PIPELINE) runs its dense
+ * stages: a hipStream_t of default priority that the caller owns and keeps
+ * alive, ideally one that the device runs beside `stream` of rec_forward()
+ * (streams share a few hardware queues; two on the same queue take turns).
+ * NULL: a stream of the library's own.  REC_ERR_STATE while dense stages are
+ * outstanding (call rec_drain() first). */
+REC_API rec_status rec_set_dense_stream(rec_model *m, void *stream);
+
+/* Pipelined models: makes `stream` wait (on the device; the host does not
+ * block) for the dense stages of every rec_forward() enqueued so far, after
+ * which their logits are ordered on `stream` like any other result.  Needed
+ * before ending a stream capture that contains pipelined forwards.  Does
+ * nothing for a model that is not pipelined. */
+REC_API rec_status rec_drain(rec_model *m, void *stream);
 
 /* Per-stage timing.  rec_set_profiling(m, slots, period) with slots > 0 makes
  * rec_forward() bracket each stage with HIP events on its stream for every
@@ -246,11 +278,14 @@ REC_API rec_status rec_set_option(rec_model *m, int32_t option, int32_t value);
  * off.  rec_stage_ms() waits for the events of `slot` and fills
  * ms[REC_NUM_STAGES]; REC_ERR_STATE if that slot has not been recorded.
  * With REC_OPT_OVERLAP_DENSE the "bottom" stage is only the time the caller's
- * stream waited for Bottom-FC after pooling had finished. */
+ * stream waited for Bottom-FC after pooling had finished.  With
+ * REC_OPT_PIPELINE the dense stages are bracketed on their own stream (a
+ * stage's time then includes whatever shared the device with it). */
 REC_API rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period);
 REC_API rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms);
 
-REC_API const char *rec_status_string(rec_status s);
+/* Text for a status; any other number gives "unknown status". */
+REC_API const char *rec_status_string(int status);
 
 #ifdef __cplusplus
 }

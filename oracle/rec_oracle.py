@@ -21,6 +21,10 @@ F32, F16 = 0, 1
 EXACT, BF16_MIRROR = 0, 1
 
 
+_LIB_SAN = os.path.join(_HERE, "librec_oracle_san.so")
+SANITIZE_ENV = "REC_ORACLE_SANITIZED"   # set (to 1): load the build below instead
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc; returns the path of the shared object."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
@@ -29,13 +33,24 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(force: bool = False) -> str:
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer (any
+    finding aborts the process).  A process that loads it must have gcc's
+    libasan preloaded; tests/test_sanitizers.py runs the pin suite that way."""
+    if force or not os.path.exists(_LIB_SAN) or os.path.getmtime(_LIB_SAN) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O1", "-g", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                               "-fno-omit-frame-pointer", "-o", _LIB_SAN, _SRC, "-lm"])
+    return _LIB_SAN
+
+
 _lib = None
 
 
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        _lib = C.CDLL(build_sanitized() if os.environ.get(SANITIZE_ENV) else build())
         _lib.oracle_half_to_double.restype = C.c_double
         _lib.oracle_half_to_double.argtypes = [C.c_uint16]
         _lib.oracle_round_bf16.restype = C.c_double

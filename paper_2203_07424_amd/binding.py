@@ -13,7 +13,9 @@ from typing import List, Optional, Sequence, Tuple
 import torch  # loads the HIP runtime the library binds to
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "librec_mi355x.so")
+# REC_MI355X_LIBRARY: another build of the same library (the host-instrumented
+# one of build.build_host_sanitized()); unset in normal use.
+LIB_PATH = os.environ.get("REC_MI355X_LIBRARY") or os.path.join(_PKG, "librec_mi355x.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -33,12 +35,13 @@ REC_DBG_OFFSETS, REC_DBG_POOLED, REC_DBG_BOTTOM_OUT, REC_DBG_INTERACT = 0, 1, 2,
 REC_OPT_OVERLAP_DENSE = 0
 REC_OPT_STREAM_ROWS = 1
 REC_OPT_FUSE_MLP = 2
+REC_OPT_PIPELINE = 3
 REC_NUM_STAGES = 6
 STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top_first", "top_rest")
 
 EXPORTS = ("rec_create", "rec_destroy", "rec_workspace_bytes", "rec_bind_workspace",
            "rec_load_tables", "rec_load_hot_rows", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_check",
-           "rec_debug_get", "rec_set_option", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
+           "rec_debug_get", "rec_set_option", "rec_set_dense_stream", "rec_drain", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
            "rec_synth_fill_table")
 
 
@@ -76,6 +79,10 @@ _lib.rec_debug_get.restype = C.c_int
 _lib.rec_debug_get.argtypes = [_vp, C.c_int32, C.POINTER(_vp), C.POINTER(C.c_int64)]
 _lib.rec_set_option.restype = C.c_int
 _lib.rec_set_option.argtypes = [_vp, C.c_int32, C.c_int32]
+_lib.rec_set_dense_stream.restype = C.c_int
+_lib.rec_set_dense_stream.argtypes = [_vp, _vp]
+_lib.rec_drain.restype = C.c_int
+_lib.rec_drain.argtypes = [_vp, _vp]
 _lib.rec_set_profiling.restype = C.c_int
 _lib.rec_set_profiling.argtypes = [_vp, C.c_int32, C.c_int32]
 _lib.rec_stage_ms.restype = C.c_int
@@ -175,6 +182,14 @@ def rec_set_option(m: int, option: int, value: int) -> int:
     return _lib.rec_set_option(m, int(option), int(value))
 
 
+def rec_set_dense_stream(m: int, stream: Optional["torch.cuda.Stream"]) -> int:
+    return _lib.rec_set_dense_stream(m, None if stream is None else stream.cuda_stream)
+
+
+def rec_drain(m: int) -> int:
+    return _lib.rec_drain(m, _stream())
+
+
 def rec_set_profiling(m: int, slots: int, period: int = 1) -> int:
     return _lib.rec_set_profiling(m, int(slots), int(period))
 
@@ -197,7 +212,8 @@ class RecModel:
     def __init__(self, num_tables: int, emb_dim: int, rows: Sequence[int], table_dtype: str,
                  num_dense: int, bottom_widths: Sequence[int], top_widths: Sequence[int],
                  max_batch: int, max_nnz: int, device: str = "cuda:0", interaction: str = "dot",
-                 towers: int = 1):
+                 towers: int = 1, pipeline: bool = False,
+                 dense_stream: Optional["torch.cuda.Stream"] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the forward pass has no CPU path")
         self.device = torch.device(device)
@@ -213,6 +229,10 @@ class RecModel:
                                      inter, towers)
         if st != REC_OK:
             raise RecError(st, "rec_create")
+        self.pipeline, self.dense_stream = bool(pipeline), dense_stream
+        if pipeline:      # decides the workspace size, so it is set before binding
+            self._ok(rec_set_option(self.handle, REC_OPT_PIPELINE, 1), "rec_set_option")
+            self._ok(rec_set_dense_stream(self.handle, dense_stream), "rec_set_dense_stream")
         self.ws = torch.empty(rec_workspace_bytes(self.handle), dtype=torch.uint8, device=self.device)
         self._ok(rec_bind_workspace(self.handle, self.ws), "rec_bind_workspace")
         self.tables: List[Optional[torch.Tensor]] = [None] * num_tables
@@ -280,6 +300,10 @@ class RecModel:
 
     def check(self) -> Tuple[int, int]:
         return rec_check(self.handle)
+
+    def drain(self) -> None:
+        """Pipelined models: orders every forward enqueued so far on the current stream."""
+        self._ok(rec_drain(self.handle), "rec_drain")
 
     def set_option(self, option: int, value: int) -> None:
         self._ok(rec_set_option(self.handle, option, value), "rec_set_option")

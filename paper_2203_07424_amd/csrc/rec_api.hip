@@ -31,6 +31,18 @@ struct Layer {
 
 }  // namespace
 
+// Where the parts of a forward's scratch memory sit inside one block of device
+// memory (byte offsets; every part 256-byte aligned).  The error record and the
+// table descriptors exist once; what one batch passes through (a frame) once
+// or twice.
+struct Frame {
+    size_t off_offsets = 0, off_tile_sums = 0, off_pooled = 0, off_x0 = 0, off_act[3] = {0, 0, 0};
+};
+struct Carve {
+    size_t off_err = 0, off_tables = 0, bytes = 0;
+    Frame fr[2];
+};
+
 struct rec_model {
     int T = 0, D = 0, F = 0, dtype = REC_F32;
     int interaction = REC_INTERACT_DOT;
@@ -46,9 +58,7 @@ struct rec_model {
     std::vector<TableDesc> desc;  // host copy of the device descriptors
     int num_cus = 256;
 
-    // workspace carve-up (byte offsets)
-    size_t off_err = 0, off_tables = 0, off_offsets = 0, off_tile_sums = 0, off_pooled = 0,
-           off_x0 = 0, off_act[3] = {0, 0, 0}, ws_bytes = 0;
+    Carve lay;               // carve-up of the bound workspace, sized for max_batch
     int z_ld = 0;            // padded width of the interaction output (act[0])
     int act_ld = 0;          // widest padded hidden activation row (elements), act[1], act[2]
     size_t act_row_bytes = 0;  // bytes of one activation row: bf16 everywhere, fp32 into the dot layer
@@ -62,14 +72,55 @@ struct rec_model {
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
+    // Sparse-dense pipeline: batches alternate between two frames of the
+    // workspace; the dense stages run on a second stream (the caller's choice,
+    // else `side`), ordered against the caller's stream by these events.
+    bool pipeline = false;
+    hipStream_t dense_stream = nullptr;
+    hipEvent_t ev_in[2] = {nullptr, nullptr}, ev_pool[2] = {nullptr, nullptr}, ev_tail[2] = {nullptr, nullptr};
+    bool tail_pending[2] = {false, false};
+    int next_frame = 0, last_frame = 0;
+
     // Stage timing: forward number i records into slot i % slots.
-    std::vector<hipEvent_t> ev;  // slots * (REC_NUM_STAGES + 1)
+    std::vector<hipEvent_t> ev;  // slots * EV_PER_SLOT
+    std::vector<char> slot_mode; // per slot: 1 if it was recorded by a pipelined forward
     int slots = 0, period = 1;
     long long forwards = 0;      // forwards seen since profiling was switched on
 
     template <class P>
     P *at(size_t off) const { return reinterpret_cast<P *>(ws + off); }
 };
+
+namespace {
+
+// Scratch layout of model m for batches of up to `batch` samples, with `frames`
+// (1 or 2) copies of the per-batch part.
+Carve carve(const rec_model *m, int batch, int frames)
+{
+    const bool concat = m->interaction == REC_INTERACT_CONCAT;
+    const size_t nb = (size_t)m->T * batch;
+    Carve c;
+    size_t o = 0;
+    c.off_err = o;    o += align_up(sizeof(ErrRecord));
+    c.off_tables = o; o += align_up(sizeof(TableDesc) * m->T);
+    for (int f = 0; f < frames; ++f) {
+        Frame &fr = c.fr[f];
+        fr.off_offsets = o;   o += align_up(sizeof(int32_t) * (nb + 1));
+        fr.off_tile_sums = o; o += align_up(sizeof(long long) * ((nb + SCAN_TILE - 1) / SCAN_TILE));
+        fr.off_pooled = o;    o += concat ? 0 : align_up(sizeof(float) * nb * m->D);
+        fr.off_x0 = o;        o += !m->bottom.empty() ? align_up(sizeof(float) * (size_t)batch * m->x0_ld) : 0;
+        // act[0] holds the Predict-FC input (kept for inspection); the hidden
+        // activations of both stacks alternate between act[1] and act[2].
+        fr.off_act[0] = o; o += align_up(2 * (size_t)batch * m->z_ld);
+        fr.off_act[1] = o; o += align_up((size_t)batch * m->act_row_bytes);
+        fr.off_act[2] = o; o += align_up((size_t)batch * m->act_row_bytes);
+    }
+    if (frames < 2) c.fr[1] = c.fr[0];
+    c.bytes = o;
+    return c;
+}
+
+}  // namespace
 
 namespace {
 
@@ -97,11 +148,280 @@ Layer *find_layer(rec_model *m, int which, int layer)
 
 }  // namespace
 
+namespace {
+
+// The buffers one forward passes through: pointers into a scratch block.
+struct Bufs {
+    ErrRecord *err;
+    const TableDesc *tables;
+    int32_t *offsets;
+    long long *tile_sums;
+    float *pooled;
+    float *x0;      // Bottom-FC output (unused without a Bottom-FC)
+    void *act[3];
+};
+
+Bufs bufs_at(char *base, const Carve &c, int frame)
+{
+    const Frame &f = c.fr[frame];
+    Bufs b;
+    b.err = reinterpret_cast<ErrRecord *>(base + c.off_err);
+    b.tables = reinterpret_cast<const TableDesc *>(base + c.off_tables);
+    b.offsets = reinterpret_cast<int32_t *>(base + f.off_offsets);
+    b.tile_sums = reinterpret_cast<long long *>(base + f.off_tile_sums);
+    b.pooled = reinterpret_cast<float *>(base + f.off_pooled);
+    b.x0 = reinterpret_cast<float *>(base + f.off_x0);
+    for (int i = 0; i < 3; ++i) b.act[i] = base + f.off_act[i];
+    return b;
+}
+
+// Arguments of one forward.
+struct Call {
+    const float *dense;
+    const int32_t *indices;
+    const int32_t *lengths;
+    int B;
+    long long nnz;
+    float *logits;
+};
+
+// Stage events of one timed forward (null: not timed).  Slot i of the array is
+// recorded by mark(i); which events bracket which stage depends on where the
+// stages were enqueued (stage_events()).
+enum { EV_BEGIN = 0, EV_SCAN_END = 1, EV_POOL_END = 2, EV_BOTTOM_END = 3, EV_INTERACT_END = 4,
+       EV_TOP_FIRST_END = 5, EV_END = 6, EV_BOTTOM_BEGIN = 7, EV_INTERACT_BEGIN = 8, EV_PER_SLOT = 9 };
+
+inline hipError_t mark(hipEvent_t *ev, int which, hipStream_t s)
+{
+    return ev ? hipEventRecord(ev[which], s) : hipSuccess;
+}
+
+#define REC_TRY(call)                          \
+    do {                                       \
+        const hipError_t e_ = (call);          \
+        if (e_ != hipSuccess) return e_;       \
+    } while (0)
+
+// A run of chain layers [i, j) of one or several stacks side by side, layer l of
+// stack k being layers[k * per_stack + l].
+void chain_run(const Layer *layers, int per_stack, int G, int i, int j, ChainProblem &c)
+{
+    c.n_layers = j - i;
+    c.groups = G;
+    c.K = layers[i].K;
+    for (int l = i; l < j; ++l) {
+        c.Kpad[l - i] = layers[l].Kpad;
+        c.Npad[l - i] = layers[l].Npad;
+        c.relu[l - i] = 1;
+        for (int k = 0; k < G; ++k) {
+            c.W[l - i][k] = layers[(size_t)k * per_stack + l].Wc;
+            c.bias[l - i][k] = layers[(size_t)k * per_stack + l].bias;
+        }
+    }
+}
+
+// How far a chain that starts at layer i of n reaches (i: no chain here).  Every
+// block of a chain streams all weights of its run, which costs more than the
+// launches it saves once they no longer are a small fraction of a block's L1
+// bandwidth over a launch time: left to itself (fuse_mlp == 1) the library
+// chains runs of up to CHAIN_AUTO_BYTES of weights, and only where that saves
+// a launch (dot_after: the one-output layer follows layer n - 1).
+int chain_end(const rec_model *m, const Layer *layers, int i, int n, bool dot_after)
+{
+    constexpr size_t CHAIN_AUTO_BYTES = 256 * 1024;
+    if (m->fuse_mlp == 0) return i;
+    int j = i;
+    size_t bytes = 0;
+    while (j < n && layers[j].chain && j - i < CHAIN_MAX_LAYERS) bytes += layers[j++].chain_bytes();
+    if (m->fuse_mlp == 2 || j == i) return j;
+    const int saved = (j - i - 1) + (dot_after && j == n && !fc_can_fuse_dot(layers[j - 1].Npad) ? 1 : 0);
+    return bytes > CHAIN_AUTO_BYTES || saved < 1 ? i : j;
+}
+
+// S2: ReLU after every layer; the last one leaves fp32 for the interaction.
+hipError_t enqueue_bottom(const rec_model *m, const Bufs &u, const Call &c, hipStream_t s)
+{
+    const int n = (int)m->bottom.size();
+    const Layer *layers = m->bottom.data();
+    const void *A = c.dense;
+    bool a_f32 = true;
+    int lda = m->F, launches = 0;
+    for (int i = 0; i < n;) {
+        const int j = chain_end(m, layers, i, n, false);
+        const int upto = j > i ? j : i + 1;
+        const bool last = upto == n;
+        void *C = last ? static_cast<void *>(u.x0) : u.act[1 + (launches & 1)];
+        const int ldc = last ? m->x0_ld : m->act_ld;
+        if (j > i) {
+            ChainProblem cp{};
+            cp.A = A; cp.a_f32 = a_f32; cp.lda = lda; cp.a_stride = 0; cp.M = c.B;
+            chain_run(layers, n, 1, i, j, cp);
+            cp.out_mode = last ? CHAIN_OUT_F32 : CHAIN_OUT_BF16;
+            cp.C = C; cp.ldc = ldc; cp.c_stride = 0;
+            REC_TRY(launch_mlp_chain(cp, s));
+        } else {
+            const Layer &l = layers[i];
+            FcProblem p{};
+            p.A = A; p.a_f32 = a_f32; p.lda = lda;
+            p.M = c.B; p.relu = true; p.groups = 1; p.num_cus = m->num_cus;
+            p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
+            p.g.W[0] = l.W; p.g.bias[0] = l.bias;
+            p.C = C; p.out_f32 = last; p.ldc = ldc;
+            REC_TRY(launch_fc(p, s));
+        }
+        A = C; lda = ldc; a_f32 = false;
+        ++launches;
+        i = upto;
+    }
+    return hipSuccess;
+}
+
+// S0 and S1.  With hot lists registered (and use_hot), hot rows are served from
+// LDS.  In the concatenation model the sums go straight into the Predict-FC
+// input rows.
+hipError_t enqueue_sparse(const rec_model *m, const Bufs &u, const Call &c, bool use_hot, hipStream_t s,
+                          hipEvent_t *ev)
+{
+    const int B = c.B, T = m->T, D = m->D;
+    const bool concat = m->interaction == REC_INTERACT_CONCAT;
+    REC_TRY(launch_scan(c.lengths, T * B, c.nnz, u.offsets, u.tile_sums, u.err, s));
+    REC_TRY(mark(ev, EV_SCAN_END, s));
+    int hmax = 0;
+    if (use_hot)
+        for (const TableDesc &d : m->desc) hmax = d.n_hot > hmax ? d.n_hot : hmax;
+    if (hmax > 0 && !concat) {
+        // Capacity: at least the longest list; a sparse hash (128 slots of rows
+        // or more, where LDS allows) keeps the per-wave probe chains short.
+        const int rowbytes = D * (m->dtype == REC_F16 ? 2 : 4);
+        int hcap = 16;
+        while (hcap < hmax) hcap *= 2;
+        while (hcap < 128 && pool_hot_fits(hcap * 2, rowbytes)) hcap *= 2;
+        REC_TRY(launch_pool_hot(u.tables, m->dtype, T, D, B, c.indices, u.offsets, u.pooled, hcap,
+                                m->num_cus, u.err, s));
+    } else {
+        const PoolOut out = concat ? PoolOut{nullptr, u.act[0], m->z_ld, m->w0}
+                                   : PoolOut{u.pooled, nullptr, 0, 0};
+        REC_TRY(launch_pool(u.tables, m->dtype, T, D, B, c.indices, u.offsets, out, c.nnz, m->stream_rows,
+                            m->max_rows, u.err, s));
+    }
+    return mark(ev, EV_POOL_END, s);
+}
+
+// S3 and S4.
+hipError_t enqueue_tail(const rec_model *m, const Bufs &u, const Call &c, hipStream_t s, hipEvent_t *ev)
+{
+    const int B = c.B, T = m->T, D = m->D;
+    const bool concat = m->interaction == REC_INTERACT_CONCAT;
+    // Without a Bottom-FC the dense part of the Predict-FC input is the dense input.
+    const float *x0 = m->bottom.empty() ? c.dense : u.x0;
+    const int x0_ld = m->bottom.empty() ? m->F : m->x0_ld;
+    // S3 -> act[0], row stride z_ld, zero filled up to it
+    if (concat)
+        REC_TRY(launch_concat_dense(x0, x0_ld, m->w0, B, u.act[0], m->z_width, m->z_ld, s));
+    else
+        REC_TRY(launch_interact(x0, x0_ld, u.pooled, B, T, D, u.act[0], m->z_ld, s));
+    REC_TRY(mark(ev, EV_INTERACT_END, s));
+    // S4: the towers run side by side, their hidden activations in adjacent
+    // column blocks of one row.  ReLU on all layers but the last.  The last layer
+    // is one fp32 dot per sample and tower: folded into the epilogue of the layer
+    // before it when that layer's block tile spans whole rows, else that layer
+    // leaves fp32 for a dot kernel.
+    const int G = m->towers, n_top = m->n_top;
+    FcProblem p{};
+    p.A = u.act[0]; p.a_f32 = false; p.lda = m->z_ld; p.a_stride = 0;
+    p.M = B; p.relu = true; p.groups = G; p.num_cus = m->num_cus;
+    for (int k = 0; k < G; ++k) {
+        const Layer &dotl = m->top[(size_t)k * n_top + n_top - 1];
+        p.g.dot_w[k] = static_cast<const float *>(dotl.W);
+        p.g.dot_bias[k] = dotl.bias;
+    }
+    bool cur_f32 = false, done = false, first_marked = false;
+    const Layer *layers = m->top.data();
+    const int n = n_top - 1;  // layers ahead of the one-output layer
+    int launches = 0;
+    for (int i = 0; i < n && !done;) {
+        const Layer &l = layers[i];  // shape of layer i in every tower
+        const int j = chain_end(m, layers, i, n, true);
+        if (j > i) {
+            ChainProblem cp{};
+            cp.A = p.A; cp.a_f32 = false; cp.lda = p.lda; cp.a_stride = p.a_stride; cp.M = B;
+            chain_run(layers, n_top, G, i, j, cp);
+            if (j == n) {
+                cp.out_mode = CHAIN_OUT_DOT;
+                for (int k = 0; k < G; ++k) { cp.dot_w[k] = p.g.dot_w[k]; cp.dot_bias[k] = p.g.dot_bias[k]; }
+                cp.dot_out = c.logits; cp.dot_ld = G;
+                done = true;
+            } else {
+                cp.out_mode = CHAIN_OUT_BF16;
+                cp.C = u.act[1 + (launches & 1)]; cp.ldc = G * layers[j - 1].Npad; cp.c_stride = layers[j - 1].Npad;
+                p.A = cp.C; p.lda = cp.ldc; p.a_stride = cp.c_stride; p.a_f32 = false;
+            }
+            REC_TRY(launch_mlp_chain(cp, s));
+            i = j;
+        } else {
+            for (int k = 0; k < G; ++k) {
+                p.g.W[k] = m->top[(size_t)k * n_top + i].W;
+                p.g.bias[k] = m->top[(size_t)k * n_top + i].bias;
+            }
+            p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
+            const bool feeds_dot = i + 1 == n;
+            if (feeds_dot && fc_can_fuse_dot(l.Npad)) {
+                p.C = nullptr; p.out_f32 = false; p.ldc = 0; p.c_stride = 0;
+                p.dot_out = c.logits; p.dot_ld = G;
+                REC_TRY(launch_fc(p, s));
+                done = true;
+            } else {
+                p.C = u.act[1 + (launches & 1)]; p.out_f32 = feeds_dot; p.ldc = G * l.Npad; p.c_stride = l.Npad;
+                REC_TRY(launch_fc(p, s));
+                p.A = p.C; p.lda = p.ldc; p.a_stride = p.c_stride; p.a_f32 = false;
+                cur_f32 = feeds_dot;
+            }
+            ++i;
+        }
+        ++launches;
+        if (!first_marked) {  // the first launch (the widest layer, or the run it starts) is timed on its own
+            REC_TRY(mark(ev, EV_TOP_FIRST_END, s));
+            first_marked = true;
+        }
+    }
+    if (!done)
+        REC_TRY(launch_rowdot(p.A, cur_f32, p.lda, p.a_stride, B, m->top[n_top - 1].Kpad, p.g, G, c.logits, G, s));
+    if (!first_marked) REC_TRY(mark(ev, EV_TOP_FIRST_END, s));
+    return mark(ev, EV_END, s);
+}
+
+// The whole pass in order on one stream: S0, S1, S2, S3, S4.
+hipError_t enqueue_in_order(const rec_model *m, const Bufs &u, const Call &c, bool use_hot, hipStream_t s,
+                            hipEvent_t *ev)
+{
+    REC_TRY(mark(ev, EV_BEGIN, s));
+    REC_TRY(enqueue_sparse(m, u, c, use_hot, s, ev));
+    REC_TRY(enqueue_bottom(m, u, c, s));
+    REC_TRY(mark(ev, EV_BOTTOM_END, s));
+    return enqueue_tail(m, u, c, s, ev);
+}
+
+// Host-checkable faults of a forward call.
+rec_status check_call(const rec_model *m, const float *dev_dense, const int32_t *dev_indices,
+                      const int32_t *dev_lengths, int32_t batch, int64_t nnz, const float *dev_logits)
+{
+    if (!m) return REC_ERR_ARG;
+    if (batch < 0 || batch > m->max_batch || nnz < 0 || nnz > m->max_nnz) return REC_ERR_ARG;
+    if (!m->ws || !all_loaded(m)) return REC_ERR_STATE;
+    if (batch == 0) return REC_OK;
+    if (!dev_dense || !dev_lengths || !dev_logits || (nnz > 0 && !dev_indices)) return REC_ERR_ARG;
+    return REC_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
-const char *rec_status_string(rec_status s)
+const char *rec_status_string(int status)
 {
-    switch (s) {
+    // An int, not the enum: a caller may pass a number that is no enumerator, and
+    // reading such a value through the enum type is undefined in C++.
+    switch (status) {
     case REC_OK: return "ok";
     case REC_ERR_ARG: return "bad argument";
     case REC_ERR_SHAPE: return "layer widths or embedding size do not fit the model";
@@ -189,20 +509,7 @@ rec_status rec_create(const rec_config *cfg, rec_model **out)
     if (cfg->n_top > 1)  // the layer feeding the dot leaves fp32
         m->act_row_bytes = std::max(m->act_row_bytes, sizeof(float) * towers * m->top[cfg->n_top - 2].Npad);
 
-    const size_t nb = (size_t)T * m->max_batch;
-    size_t o = 0;
-    m->off_err = o;       o += align_up(sizeof(ErrRecord));
-    m->off_tables = o;    o += align_up(sizeof(TableDesc) * T);
-    m->off_offsets = o;   o += align_up(sizeof(int32_t) * (nb + 1));
-    m->off_tile_sums = o; o += align_up(sizeof(long long) * ((nb + SCAN_TILE - 1) / SCAN_TILE));
-    m->off_pooled = o;    o += concat ? 0 : align_up(sizeof(float) * nb * D);
-    m->off_x0 = o;        o += cfg->n_bottom > 0 ? align_up(sizeof(float) * (size_t)m->max_batch * m->x0_ld) : 0;
-    // act[0] holds the Predict-FC input (kept for inspection); the hidden
-    // activations of both stacks alternate between act[1] and act[2].
-    m->off_act[0] = o; o += align_up(2 * (size_t)m->max_batch * m->z_ld);
-    m->off_act[1] = o; o += align_up((size_t)m->max_batch * m->act_row_bytes);
-    m->off_act[2] = o; o += align_up((size_t)m->max_batch * m->act_row_bytes);
-    m->ws_bytes = o;
+    m->lay = carve(m, m->max_batch, 1);
     *out = m;
     return REC_OK;
 }
@@ -214,23 +521,33 @@ void rec_destroy(rec_model *m)
         if (e) (void)hipEventDestroy(e);
     if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
     if (m->ev_join) (void)hipEventDestroy(m->ev_join);
+    for (int k = 0; k < 2; ++k)
+        for (hipEvent_t e : {m->ev_in[k], m->ev_pool[k], m->ev_tail[k]})
+            if (e) (void)hipEventDestroy(e);
     if (m->side) (void)hipStreamDestroy(m->side);
     delete m;
 }
 
-size_t rec_workspace_bytes(const rec_model *m) { return m ? m->ws_bytes : 0; }
+size_t rec_workspace_bytes(const rec_model *m) { return m ? m->lay.bytes : 0; }
 
 rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *stream)
 {
     if (!m || !dev_ptr) return REC_ERR_ARG;
-    if (bytes < m->ws_bytes || reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return REC_ERR_ARG;
+    if (bytes < m->lay.bytes || reinterpret_cast<uintptr_t>(dev_ptr) % ALIGN != 0) return REC_ERR_ARG;
     if (!m->side) {
         // Default priority; the two events only order work, they carry no timing.
         if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
             hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess)
             return REC_ERR_DEVICE;
+        for (int k = 0; k < 2; ++k)
+            if (hipEventCreateWithFlags(&m->ev_in[k], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&m->ev_pool[k], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&m->ev_tail[k], hipEventDisableTiming) != hipSuccess)
+                return REC_ERR_DEVICE;
     }
+    m->tail_pending[0] = m->tail_pending[1] = false;
+    m->next_frame = m->last_frame = 0;
     if (fc_big_prepare() != hipSuccess || chain_prepare() != hipSuccess) return REC_ERR_DEVICE;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
@@ -241,7 +558,7 @@ rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *s
     std::fill(m->table_loaded.begin(), m->table_loaded.end(), 0);
     for (TableDesc &d : m->desc) { d.base = nullptr; d.hot_ids = nullptr; d.n_hot = 0; }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (launch_clear_err(m->at<ErrRecord>(m->off_err), s) != hipSuccess) return REC_ERR_DEVICE;
+    if (launch_clear_err(m->at<ErrRecord>(m->lay.off_err), s) != hipSuccess) return REC_ERR_DEVICE;
     if (hipStreamSynchronize(s) != hipSuccess) return REC_ERR_DEVICE;
     return REC_OK;
 }
@@ -252,7 +569,7 @@ rec_status rec_load_tables(rec_model *m, int32_t table, const void *dev_rows)
     if (reinterpret_cast<uintptr_t>(dev_rows) % 16 != 0) return REC_ERR_ARG;
     if (!m->ws) return REC_ERR_STATE;
     m->desc[table].base = dev_rows;
-    if (hipMemcpy(m->at<TableDesc>(m->off_tables) + table, &m->desc[table], sizeof(TableDesc),
+    if (hipMemcpy(m->at<TableDesc>(m->lay.off_tables) + table, &m->desc[table], sizeof(TableDesc),
                   hipMemcpyHostToDevice) != hipSuccess)
         return REC_ERR_DEVICE;
     m->table_loaded[table] = 1;
@@ -270,7 +587,7 @@ rec_status rec_load_hot_rows(rec_model *m, int32_t table, const int32_t *dev_ids
     if (n > 0 && !pool_hot_fits(hcap, rowbytes)) return REC_ERR_ARG;
     m->desc[table].hot_ids = n > 0 ? dev_ids : nullptr;
     m->desc[table].n_hot = n;
-    if (hipMemcpy(m->at<TableDesc>(m->off_tables) + table, &m->desc[table], sizeof(TableDesc),
+    if (hipMemcpy(m->at<TableDesc>(m->lay.off_tables) + table, &m->desc[table], sizeof(TableDesc),
                   hipMemcpyHostToDevice) != hipSuccess)
         return REC_ERR_DEVICE;
     return REC_OK;
@@ -312,230 +629,90 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
                        const int32_t *dev_lengths, int32_t batch, int64_t nnz, float *dev_logits,
                        void *stream)
 {
-    if (!m) return REC_ERR_ARG;
-    if (batch < 0 || batch > m->max_batch || nnz < 0 || nnz > m->max_nnz) return REC_ERR_ARG;
-    if (!m->ws || !all_loaded(m)) return REC_ERR_STATE;
-    if (batch == 0) return REC_OK;
-    if (!dev_dense || !dev_lengths || !dev_logits || (nnz > 0 && !dev_indices)) return REC_ERR_ARG;
+    const rec_status st = check_call(m, dev_dense, dev_indices, dev_lengths, batch, nnz, dev_logits);
+    if (st != REC_OK || batch == 0) return st;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int B = batch, T = m->T, D = m->D;
-    const bool concat = m->interaction == REC_INTERACT_CONCAT;
-    ErrRecord *err = m->at<ErrRecord>(m->off_err);
-    int32_t *offsets = m->at<int32_t>(m->off_offsets);
-    float *pooled = m->at<float>(m->off_pooled);
-    // Without a Bottom-FC the dense part of the Predict-FC input is the dense input.
-    const float *x0 = m->bottom.empty() ? dev_dense : m->at<float>(m->off_x0);
-    const int x0_ld = m->bottom.empty() ? m->F : m->x0_ld;
-    void *act[3] = {m->at<void>(m->off_act[0]), m->at<void>(m->off_act[1]),
-                    m->at<void>(m->off_act[2])};
+    const Call c{dev_dense, dev_indices, dev_lengths, batch, nnz, dev_logits};
     // Forward number i is timed when i is a multiple of the period; it is the
     // (i / period)-th timed one.
     const bool prof = m->slots > 0 && m->forwards % m->period == 0;
-    hipEvent_t *ev = prof ? &m->ev[(size_t)((m->forwards / m->period) % m->slots) * (REC_NUM_STAGES + 1)]
-                          : nullptr;
-    int stage = 0;
-#define REC_MARK()                                                                      \
-    do {                                                                                \
-        if (prof && hipEventRecord(ev[stage++], s) != hipSuccess) return REC_ERR_DEVICE;   \
-    } while (0)
-#define REC_TRY(call)                                  \
+    const size_t slot = prof ? (size_t)((m->forwards / m->period) % m->slots) : 0;
+    hipEvent_t *ev = prof ? &m->ev[slot * EV_PER_SLOT] : nullptr;
+#define REC_DEV(call)                                  \
     do {                                               \
         if ((call) != hipSuccess) return REC_ERR_DEVICE; \
     } while (0)
 
-    // S2 does not depend on S0/S1: with overlap it is enqueued on the side
-    // stream, forked from and joined back into the caller's stream.
-    const bool overlap = m->overlap_dense && !m->bottom.empty();
-    hipStream_t sd = overlap ? m->side : s;
-    // A run of chain layers [i, j) of one or several stacks side by side, layer l of
-    // stack k being layers[k * per_stack + l].
-    auto chain_run = [&](const Layer *layers, int per_stack, int G, int i, int j, ChainProblem &c) {
-        c.n_layers = j - i;
-        c.groups = G;
-        c.K = layers[i].K;
-        for (int l = i; l < j; ++l) {
-            c.Kpad[l - i] = layers[l].Kpad;
-            c.Npad[l - i] = layers[l].Npad;
-            c.relu[l - i] = 1;
-            for (int k = 0; k < G; ++k) {
-                c.W[l - i][k] = layers[(size_t)k * per_stack + l].Wc;
-                c.bias[l - i][k] = layers[(size_t)k * per_stack + l].bias;
-            }
+    if (m->pipeline) {
+        // Sparse stage (S0, S1) on the caller's stream, dense stages (S2; S3, S4)
+        // on the second stream: the dense stages of this batch run beside the
+        // sparse stage of the next one (Sec. IV-A, S-D pipeline).  Frame k holds
+        // what this batch passes through; the batch before it used the other one.
+        const int k = m->next_frame;
+        const Bufs u = bufs_at(m->ws, m->lay, k);
+        hipStream_t d = m->dense_stream ? m->dense_stream : m->side;
+        // The inputs are ready at this point of the caller's stream.
+        REC_DEV(hipEventRecord(m->ev_in[k], s));
+        REC_DEV(hipStreamWaitEvent(d, m->ev_in[k], 0));
+        if (!m->bottom.empty()) {
+            REC_DEV(mark(ev, EV_BOTTOM_BEGIN, d));
+            REC_DEV(enqueue_bottom(m, u, c, d));
+            REC_DEV(mark(ev, EV_BOTTOM_END, d));
         }
-    };
-    // How far a chain that starts at layer i of n reaches (i: no chain here).  Every
-    // block of a chain streams all weights of its run, which costs more than the
-    // launches it saves once they no longer are a small fraction of a block's L1
-    // bandwidth over a launch time: left to itself (fuse_mlp == 1) the library
-    // chains runs of up to CHAIN_AUTO_BYTES of weights, and only where that saves
-    // a launch (dot_after: the one-output layer follows layer n - 1).
-    constexpr size_t CHAIN_AUTO_BYTES = 256 * 1024;
-    auto chain_end = [&](const Layer *layers, int i, int n, bool dot_after) {
-        if (m->fuse_mlp == 0) return i;
-        int j = i;
-        size_t bytes = 0;
-        while (j < n && layers[j].chain && j - i < CHAIN_MAX_LAYERS) bytes += layers[j++].chain_bytes();
-        if (m->fuse_mlp == 2 || j == i) return j;
-        const int saved = (j - i - 1) + (dot_after && j == n && !fc_can_fuse_dot(layers[j - 1].Npad) ? 1 : 0);
-        return bytes > CHAIN_AUTO_BYTES || saved < 1 ? i : j;
-    };
-    auto bottom_fc = [&]() -> hipError_t {
-        // ReLU after every layer; the last one leaves fp32 for the interaction.
-        const int n = (int)m->bottom.size();
-        const Layer *layers = m->bottom.data();
-        const void *A = dev_dense;
-        bool a_f32 = true;
-        int lda = m->F, launches = 0;
-        for (int i = 0; i < n;) {
-            const int j = chain_end(layers, i, n, false);
-            const int upto = j > i ? j : i + 1;
-            const bool last = upto == n;
-            void *C = last ? static_cast<void *>(m->at<float>(m->off_x0)) : act[1 + (launches & 1)];
-            const int ldc = last ? m->x0_ld : m->act_ld;
-            hipError_t e;
-            if (j > i) {
-                ChainProblem c{};
-                c.A = A; c.a_f32 = a_f32; c.lda = lda; c.a_stride = 0; c.M = B;
-                chain_run(layers, n, 1, i, j, c);
-                c.out_mode = last ? CHAIN_OUT_F32 : CHAIN_OUT_BF16;
-                c.C = C; c.ldc = ldc; c.c_stride = 0;
-                e = launch_mlp_chain(c, sd);
-            } else {
-                const Layer &l = layers[i];
-                FcProblem p{};
-                p.A = A; p.a_f32 = a_f32; p.lda = lda;
-                p.M = B; p.relu = true; p.groups = 1; p.num_cus = m->num_cus;
-                p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
-                p.g.W[0] = l.W; p.g.bias[0] = l.bias;
-                p.C = C; p.out_f32 = last; p.ldc = ldc;
-                e = launch_fc(p, sd);
-            }
-            if (e != hipSuccess) return e;
-            A = C; lda = ldc; a_f32 = false;
-            ++launches;
-            i = upto;
+        REC_DEV(mark(ev, EV_BEGIN, s));
+        REC_DEV(enqueue_sparse(m, u, c, true, s, ev));
+        REC_DEV(hipEventRecord(m->ev_pool[k], s));
+        // The dense stages of the batch before this one have had a whole
+        // pooling launch to finish: behind it the caller's stream waits for
+        // them, which makes their logits visible to it and frees their frame.
+        if (m->tail_pending[k ^ 1]) {
+            REC_DEV(hipStreamWaitEvent(s, m->ev_tail[k ^ 1], 0));
+            m->tail_pending[k ^ 1] = false;
         }
-        return hipSuccess;
-    };
-
-    REC_MARK();
-    if (overlap) {
-        REC_TRY(hipEventRecord(m->ev_fork, s));
-        REC_TRY(hipStreamWaitEvent(sd, m->ev_fork, 0));
-        REC_TRY(bottom_fc());
-        REC_TRY(hipEventRecord(m->ev_join, sd));
-    }
-    // S0
-    REC_TRY(launch_scan(dev_lengths, T * B, nnz, offsets, m->at<long long>(m->off_tile_sums), err, s));
-    REC_MARK();
-    // S1: with hot lists registered, hot rows are served from LDS.  In the
-    // concatenation model the sums go straight into the Predict-FC input rows.
-    {
-        int hmax = 0;
-        for (const TableDesc &d : m->desc) hmax = d.n_hot > hmax ? d.n_hot : hmax;
-        if (hmax > 0 && !concat) {
-            // Capacity: at least the longest list; a sparse hash (128 slots of rows
-            // or more, where LDS allows) keeps the per-wave probe chains short.
-            const int rowbytes = D * (m->dtype == REC_F16 ? 2 : 4);
-            int hcap = 16;
-            while (hcap < hmax) hcap *= 2;
-            while (hcap < 128 && pool_hot_fits(hcap * 2, rowbytes)) hcap *= 2;
-            REC_TRY(launch_pool_hot(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
-                                    pooled, hcap, m->num_cus, err, s));
+        REC_DEV(hipStreamWaitEvent(d, m->ev_pool[k], 0));
+        REC_DEV(mark(ev, EV_INTERACT_BEGIN, d));
+        REC_DEV(enqueue_tail(m, u, c, d, ev));
+        REC_DEV(hipEventRecord(m->ev_tail[k], d));
+        m->tail_pending[k] = true;
+        m->last_frame = k;
+        m->next_frame = k ^ 1;
+        if (prof) m->slot_mode[slot] = 1;
+    } else {
+        const Bufs u = bufs_at(m->ws, m->lay, 0);
+        m->last_frame = 0;
+        // S2 does not depend on S0/S1: with overlap it is enqueued on the side
+        // stream, forked from and joined back into the caller's stream.
+        if (m->overlap_dense && !m->bottom.empty()) {
+            REC_DEV(mark(ev, EV_BEGIN, s));
+            REC_DEV(hipEventRecord(m->ev_fork, s));
+            REC_DEV(hipStreamWaitEvent(m->side, m->ev_fork, 0));
+            REC_DEV(enqueue_bottom(m, u, c, m->side));
+            REC_DEV(hipEventRecord(m->ev_join, m->side));
+            REC_DEV(enqueue_sparse(m, u, c, true, s, ev));
+            // the "bottom" stage then times only what pooling did not hide
+            REC_DEV(hipStreamWaitEvent(s, m->ev_join, 0));
+            REC_DEV(mark(ev, EV_BOTTOM_END, s));
+            REC_DEV(enqueue_tail(m, u, c, s, ev));
         } else {
-            const PoolOut out = concat ? PoolOut{nullptr, act[0], m->z_ld, m->w0}
-                                       : PoolOut{pooled, nullptr, 0, 0};
-            REC_TRY(launch_pool(m->at<TableDesc>(m->off_tables), m->dtype, T, D, B, dev_indices, offsets,
-                                out, nnz, m->stream_rows, m->max_rows, err, s));
+            REC_DEV(enqueue_in_order(m, u, c, true, s, ev));
         }
+        if (prof) m->slot_mode[slot] = 0;
     }
-    REC_MARK();
-    // S2, or the wait for it (the "bottom" stage then times only what pooling did not hide)
-    if (overlap)
-        REC_TRY(hipStreamWaitEvent(s, m->ev_join, 0));
-    else
-        REC_TRY(bottom_fc());
-    REC_MARK();
-    // S3 -> act[0], row stride z_ld, zero filled up to it
-    if (concat)
-        REC_TRY(launch_concat_dense(x0, x0_ld, m->w0, B, act[0], m->z_width, m->z_ld, s));
-    else
-        REC_TRY(launch_interact(x0, x0_ld, pooled, B, T, D, act[0], m->z_ld, s));
-    REC_MARK();
-    // S4: the towers run side by side, their hidden activations in adjacent
-    // column blocks of one row.  ReLU on all layers but the last.  The last layer
-    // is one fp32 dot per sample and tower: folded into the epilogue of the layer
-    // before it when that layer's block tile spans whole rows, else that layer
-    // leaves fp32 for a dot kernel.
-    {
-        const int G = m->towers, n_top = m->n_top;
-        FcProblem p{};
-        p.A = act[0]; p.a_f32 = false; p.lda = m->z_ld; p.a_stride = 0;
-        p.M = B; p.relu = true; p.groups = G; p.num_cus = m->num_cus;
-        for (int k = 0; k < G; ++k) {
-            const Layer &dotl = m->top[(size_t)k * n_top + n_top - 1];
-            p.g.dot_w[k] = static_cast<const float *>(dotl.W);
-            p.g.dot_bias[k] = dotl.bias;
-        }
-        bool cur_f32 = false, done = false, first_marked = false;
-        const Layer *layers = m->top.data();
-        const int n = n_top - 1;  // layers ahead of the one-output layer
-        int launches = 0;
-        for (int i = 0; i < n && !done;) {
-            const Layer &l = layers[i];  // shape of layer i in every tower
-            const int j = chain_end(layers, i, n, true);
-            if (j > i) {
-                ChainProblem c{};
-                c.A = p.A; c.a_f32 = false; c.lda = p.lda; c.a_stride = p.a_stride; c.M = B;
-                chain_run(layers, n_top, G, i, j, c);
-                if (j == n) {
-                    c.out_mode = CHAIN_OUT_DOT;
-                    for (int k = 0; k < G; ++k) { c.dot_w[k] = p.g.dot_w[k]; c.dot_bias[k] = p.g.dot_bias[k]; }
-                    c.dot_out = dev_logits; c.dot_ld = G;
-                    done = true;
-                } else {
-                    c.out_mode = CHAIN_OUT_BF16;
-                    c.C = act[1 + (launches & 1)]; c.ldc = G * layers[j - 1].Npad; c.c_stride = layers[j - 1].Npad;
-                    p.A = c.C; p.lda = c.ldc; p.a_stride = c.c_stride; p.a_f32 = false;
-                }
-                REC_TRY(launch_mlp_chain(c, s));
-                i = j;
-            } else {
-                for (int k = 0; k < G; ++k) {
-                    p.g.W[k] = m->top[(size_t)k * n_top + i].W;
-                    p.g.bias[k] = m->top[(size_t)k * n_top + i].bias;
-                }
-                p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
-                const bool feeds_dot = i + 1 == n;
-                if (feeds_dot && fc_can_fuse_dot(l.Npad)) {
-                    p.C = nullptr; p.out_f32 = false; p.ldc = 0; p.c_stride = 0;
-                    p.dot_out = dev_logits; p.dot_ld = G;
-                    REC_TRY(launch_fc(p, s));
-                    done = true;
-                } else {
-                    p.C = act[1 + (launches & 1)]; p.out_f32 = feeds_dot; p.ldc = G * l.Npad; p.c_stride = l.Npad;
-                    REC_TRY(launch_fc(p, s));
-                    p.A = p.C; p.lda = p.ldc; p.a_stride = p.c_stride; p.a_f32 = false;
-                    cur_f32 = feeds_dot;
-                }
-                ++i;
-            }
-            ++launches;
-            if (!first_marked) {  // the first launch (the widest layer, or the run it starts) is timed on its own
-                REC_MARK();
-                first_marked = true;
-            }
-        }
-        if (!done)
-            REC_TRY(launch_rowdot(p.A, cur_f32, p.lda, p.a_stride, B, m->top[n_top - 1].Kpad, p.g, G,
-                                  dev_logits, G, s));
-        if (!first_marked) REC_MARK();
-    }
-    REC_MARK();
-#undef REC_MARK
-#undef REC_TRY
+#undef REC_DEV
     if (m->slots > 0) ++m->forwards;
+    return REC_OK;
+}
+
+rec_status rec_drain(rec_model *m, void *stream)
+{
+    if (!m) return REC_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int k = 0; k < 2; ++k)
+        if (m->tail_pending[k]) {
+            if (hipStreamWaitEvent(s, m->ev_tail[k], 0) != hipSuccess) return REC_ERR_DEVICE;
+            m->tail_pending[k] = false;
+        }
     return REC_OK;
 }
 
@@ -545,7 +722,8 @@ rec_status rec_check(rec_model *m, void *stream, int64_t *first_bad_pos)
     if (!m->ws) return REC_ERR_STATE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     ErrRecord h;
-    ErrRecord *d = m->at<ErrRecord>(m->off_err);
+    ErrRecord *d = m->at<ErrRecord>(m->lay.off_err);
+    if (rec_drain(m, stream) != REC_OK) return REC_ERR_DEVICE;
     if (hipStreamSynchronize(s) != hipSuccess) return REC_ERR_DEVICE;
     if (hipMemcpy(&h, d, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return REC_ERR_DEVICE;
     if (first_bad_pos) *first_bad_pos = -1;
@@ -565,15 +743,16 @@ rec_status rec_debug_get(rec_model *m, int32_t what, const void **dev_ptr, int64
     if (!m || !dev_ptr) return REC_ERR_ARG;
     if (!m->ws) return REC_ERR_STATE;
     int64_t ld = 0;
+    const Frame &f = m->lay.fr[m->last_frame];
     switch (what) {
-    case REC_DBG_OFFSETS: *dev_ptr = m->at<void>(m->off_offsets); ld = 0; break;
+    case REC_DBG_OFFSETS: *dev_ptr = m->at<void>(f.off_offsets); ld = 0; break;
     case REC_DBG_POOLED:
         if (m->interaction != REC_INTERACT_DOT) return REC_ERR_STATE;
-        *dev_ptr = m->at<void>(m->off_pooled); ld = m->D; break;
+        *dev_ptr = m->at<void>(f.off_pooled); ld = m->D; break;
     case REC_DBG_BOTTOM_OUT:
         if (m->bottom.empty()) return REC_ERR_STATE;
-        *dev_ptr = m->at<void>(m->off_x0); ld = m->x0_ld; break;
-    case REC_DBG_INTERACT: *dev_ptr = m->at<void>(m->off_act[0]); ld = m->z_ld; break;
+        *dev_ptr = m->at<void>(f.off_x0); ld = m->x0_ld; break;
+    case REC_DBG_INTERACT: *dev_ptr = m->at<void>(f.off_act[0]); ld = m->z_ld; break;
     default: return REC_ERR_ARG;
     }
     if (ld_out) *ld_out = ld;
@@ -590,8 +769,23 @@ rec_status rec_set_option(rec_model *m, int32_t option, int32_t value)
         if (value < 0 || value > 2) return REC_ERR_ARG;
         m->fuse_mlp = value;
         return REC_OK;
+    case REC_OPT_PIPELINE:
+        // Decides the size of the workspace: only while none is bound.
+        if (m->ws) return REC_ERR_STATE;
+        m->pipeline = value != 0;
+        m->lay = carve(m, m->max_batch, m->pipeline ? 2 : 1);
+        return REC_OK;
     default: return REC_ERR_ARG;
     }
+}
+
+rec_status rec_set_dense_stream(rec_model *m, void *stream)
+{
+    if (!m) return REC_ERR_ARG;
+    for (int k = 0; k < 2; ++k)
+        if (m->tail_pending[k]) return REC_ERR_STATE;  // work is still ordered on the old one
+    m->dense_stream = static_cast<hipStream_t>(stream);
+    return REC_OK;
 }
 
 rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period)
@@ -599,7 +793,8 @@ rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period)
     if (!m || slots < 0 || slots > 65536 || (slots > 0 && period < 1)) return REC_ERR_ARG;
     for (hipEvent_t e : m->ev)
         if (e) (void)hipEventDestroy(e);
-    m->ev.assign((size_t)slots * (REC_NUM_STAGES + 1), nullptr);
+    m->ev.assign((size_t)slots * EV_PER_SLOT, nullptr);
+    m->slot_mode.assign((size_t)slots, 0);
     m->slots = 0;
     m->forwards = 0;
     for (hipEvent_t &e : m->ev)
@@ -614,10 +809,22 @@ rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms)
     if (!m || !ms) return REC_ERR_ARG;
     const long long timed = (m->forwards + m->period - 1) / m->period;  // timed forwards so far
     if (m->slots <= 0 || slot < 0 || slot >= m->slots || slot >= timed) return REC_ERR_STATE;
-    hipEvent_t *ev = &m->ev[(size_t)slot * (REC_NUM_STAGES + 1)];
-    if (hipEventSynchronize(ev[REC_NUM_STAGES]) != hipSuccess) return REC_ERR_DEVICE;
-    for (int i = 0; i < REC_NUM_STAGES; ++i)
-        if (hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) return REC_ERR_DEVICE;
+    hipEvent_t *ev = &m->ev[(size_t)slot * EV_PER_SLOT];
+    // Stage i ran between events begin[i] and end[i]; in a pipelined forward the
+    // dense stages sit on another stream and have begin events of their own.
+    static const int end[REC_NUM_STAGES] = {EV_SCAN_END, EV_POOL_END, EV_BOTTOM_END, EV_INTERACT_END,
+                                            EV_TOP_FIRST_END, EV_END};
+    static const int begin_in_order[REC_NUM_STAGES] = {EV_BEGIN, EV_SCAN_END, EV_POOL_END, EV_BOTTOM_END,
+                                                       EV_INTERACT_END, EV_TOP_FIRST_END};
+    static const int begin_pipelined[REC_NUM_STAGES] = {EV_BEGIN, EV_SCAN_END, EV_BOTTOM_BEGIN,
+                                                        EV_INTERACT_BEGIN, EV_INTERACT_END, EV_TOP_FIRST_END};
+    const int *begin = m->slot_mode[slot] ? begin_pipelined : begin_in_order;
+    if (hipEventSynchronize(ev[EV_END]) != hipSuccess) return REC_ERR_DEVICE;
+    for (int i = 0; i < REC_NUM_STAGES; ++i) {
+        ms[i] = 0.0f;
+        if (m->slot_mode[slot] && i == REC_STAGE_BOTTOM && m->bottom.empty()) continue;
+        if (hipEventElapsedTime(&ms[i], ev[begin[i]], ev[end[i]]) != hipSuccess) return REC_ERR_DEVICE;
+    }
     return REC_OK;
 }
 

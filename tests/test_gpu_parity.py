@@ -504,53 +504,156 @@ def test_tiny_workload_full_batch(binding):
 
 
 # ------------------------------------------------------------- full-size workloads
-@pytest.mark.parametrize("name,n_check", [("rmc3", 24), ("rmc1", 24), ("rmc2", 24)])
-def test_full_size_workload_sampled_against_oracle(binding, name, n_check):
-    """The named workload at its full size, in the launch configuration the
-    benchmark times; the oracle recomputes a spread of samples one by one."""
-    w = synth.WORKLOADS[name]
-    say("full-size workload", name)
-    m, bottom, top = H.make_workload_model(binding, w)
-    batch = synth.draw_batch(w, 0)
-    logits = H.run(m, batch)
+# Device and bf16 mirror narrow the same values, but from slightly different
+# sums (fp32 and split-bf16 accumulation against fp64), so a few per cent of the
+# narrowed interaction terms land on the other side of a bf16 rounding boundary
+# (one unit in the last place, 2^-8 of the term); over a whole 4096-batch the
+# worst sample collects a little more of that than the 5e-3 small shapes use.
+WHOLE_BATCH_MIRROR_RTOL = 1e-2
+
+
+def whole_batch_check(binding, m, w, batch, logits, bottom, top, label):
+    """Every sample of a full-size batch against the oracle: offsets bit for bit,
+    pooled sums and logits to the bars of gpu_helpers."""
     assert m.check() == (binding.REC_OK, -1)
     off = m.debug_offsets().cpu().numpy()
     assert off[0] == 0 and off[-1] == batch.nnz
     assert np.array_equal(np.diff(off.astype(np.int64)), batch.lengths)
-    g = np.random.default_rng(5)
-    pick = np.unique(np.concatenate([[0, 1, w.batch // 2, w.batch - 2, w.batch - 1],
-                                     g.integers(0, w.batch, n_check)]))
-    exact = H.oracle_on_slice(w, batch, pick, bottom, top)
-    mirror = H.oracle_on_slice(w, batch, pick, bottom, top, orc.BF16_MIRROR)
-    pooled = m.debug_pooled()[torch.from_numpy(pick).cuda()].cpu().numpy()
-    H.check_pooled(pooled, exact["pooled"], exact["abs_sum"])
-    H.check_logits(logits[pick], exact["logits"], mirror["logits"])
-    assert np.isfinite(logits).all()
+    exact, mirror, P, A = H.oracle_on_batch(w, batch, bottom, top)
+    cols = (logits.reshape(w.batch, -1), exact["logits"].reshape(w.batch, -1),
+            mirror["logits"].reshape(w.batch, -1))
+    for k in range(cols[0].shape[1]):
+        re, rm = H.per_sample_ratio(cols[0][:, k], cols[1][:, k]), H.per_sample_ratio(cols[0][:, k], cols[2][:, k])
+        say(f"{label} tower {k}: per-sample |g-o| / max(|o|, rms) vs the exact oracle: median {np.median(re):.2e} "
+            f"p99 {np.percentile(re, 99):.2e} worst {re.max():.2e}, {(re > H.LOGIT_RTOL).sum()} of {w.batch} "
+            f"beyond 2e-2; vs the bf16 mirror: median {np.median(rm):.2e} p99 {np.percentile(rm, 99):.2e} "
+            f"worst {rm.max():.2e}")
+    if w.interaction == "dot":
+        H.check_pooled(m.debug_pooled().cpu().numpy(), P, A)
+    H.check_logits(logits, exact["logits"], mirror["logits"], mirror_rtol=WHOLE_BATCH_MIRROR_RTOL)
+    # Per sample, |g - o| <= 2e-2 max(|o|, rms) against the exact oracle, except
+    # where bf16 operands themselves (the oracle's mirror: same narrowing points,
+    # fp64 sums, no device involved) already leave the sample beyond that: one
+    # sample in a few thousand does, by a few per cent of the bound.
+    for k in range(cols[0].shape[1]):
+        re = H.per_sample_ratio(cols[0][:, k], cols[1][:, k])
+        rme = H.per_sample_ratio(cols[2][:, k], cols[1][:, k])
+        say(f"{label} tower {k}: the mirror itself is beyond 2e-2 of the exact oracle on {(rme > H.LOGIT_RTOL).sum()} "
+            f"samples (worst {rme.max():.2e})")
+        assert (re <= np.maximum(H.LOGIT_RTOL, rme + 2e-3)).all(), (k, float(re.max()))
+        assert (re > H.LOGIT_RTOL).sum() <= max(1, w.batch // 1000), int((re > H.LOGIT_RTOL).sum())
+
+
+@pytest.mark.parametrize("name,uniform", [("rmc3", False), ("rmc1", False), ("rmc2", False), ("rmc2", True)])
+def test_full_size_workload_whole_batch_against_oracle(binding, name, uniform):
+    """The named workload at its full size, in the launch configuration the
+    benchmark times (uniform ids: row loads with the non-temporal hint, the
+    leg the HBM figure is quoted on); the oracle recomputes EVERY sample."""
+    w = synth.WORKLOADS[name]
+    if uniform:
+        w = w.with_uniform_indices()
+    say("full-size workload, whole batch", w.name)
+    m, bottom, top = H.make_workload_model(binding, w)
+    m.set_option(binding.REC_OPT_STREAM_ROWS, int(w.index_dist[0] == "uniform"))
+    batch = synth.draw_batch(w, 0)
+    logits = H.run(m, batch)
+    whole_batch_check(binding, m, w, batch, logits, bottom, top, w.name)
     m.close()
     torch.cuda.empty_cache()
 
 
+def test_co_located_instances_whole_batch_against_oracle(binding):
+    """Two instances sharing the tables, each on a stream of its own, forwards
+    interleaved without synchronisation (the benchmark's co-located leg): both
+    logits buffers against the oracle, and bit-equal to a forward run alone."""
+    w = synth.WORKLOADS["rmc2"]
+    say("co-located instances", w.name)
+    m0, bottom, top = H.make_workload_model(binding, w)
+    m1, _, _ = H.make_workload_model(binding, w, share_tables=m0)
+    models, streams = [m0, m1], [torch.cuda.Stream(), torch.cuda.Stream()]
+    batches = [synth.draw_batch(w, 10 + i) for i in range(2)]
+    dev = [(torch.from_numpy(b.dense).cuda(), torch.from_numpy(b.indices).cuda(),
+            torch.from_numpy(b.lengths).cuda()) for b in batches]
+    alone = [H.run(m0, b) for b in batches]
+    outs = [[torch.empty(w.batch, dtype=torch.float32, device="cuda") for _ in range(2)] for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(3):                            # instance k takes batch (rep + k) % 2
+        for k in range(2):
+            with torch.cuda.stream(streams[k]):
+                models[k].forward(*dev[(rep + k) % 2], outs[k][(rep + k) % 2])
+    torch.cuda.synchronize()
+    for k in range(2):
+        assert models[k].check() == (binding.REC_OK, -1)
+        for j in range(2):
+            assert np.array_equal(outs[k][j].cpu().numpy(), alone[j]), (k, j)
+    for j in range(2):
+        exact, mirror, _, _ = H.oracle_on_batch(w, batches[j], bottom, top)
+        H.check_logits(alone[j], exact["logits"], mirror["logits"], mirror_rtol=WHOLE_BATCH_MIRROR_RTOL)
+    m1.close()
+    m0.close()
+    torch.cuda.empty_cache()
+
+
+def test_forward_rejects_buffers_smaller_than_the_call_says(binding):
+    """The C boundary sees pointers only, so the binding checks sizes before the
+    call: a [B] logits buffer for a model with several towers (which once let the
+    device write past it), short lengths, short dense.  Nothing is enqueued."""
+    say("undersized buffers")
+    w = synth.WORKLOADS["mtwnd-tiny"]
+    m, _, _ = H.make_workload_model(binding, w)
+    batch = synth.draw_batch(w, 0)
+    d, i, l = (torch.from_numpy(x).cuda() for x in (batch.dense, batch.indices, batch.lengths))
+    B = w.batch
+    with pytest.raises(ValueError):
+        m.forward(d, i, l, torch.empty(B, dtype=torch.float32, device="cuda"))          # needs [B][3]
+    with pytest.raises(ValueError):
+        m.forward(d, i, l[:-1].contiguous())
+    with pytest.raises(ValueError):
+        m.forward(d[:, :-1].contiguous(), i, l)
+    with pytest.raises(ValueError):
+        m.forward(d, i.to(torch.int64), l)
+    with pytest.raises(ValueError):
+        m.forward(d, i, l, torch.empty((B, w.towers), dtype=torch.float32))               # host tensor
+    out = m.forward(d, i, l, torch.empty((B, w.towers), dtype=torch.float32, device="cuda"))
+    torch.cuda.synchronize()
+    assert m.check() == (binding.REC_OK, -1) and torch.isfinite(out).all()
+    m.close()
+
+
 def test_large_capacity_variant_sampled_against_oracle(binding):
     """154 GB of tables: rows sit beyond 2 GiB inside a table, so this is the
-    case that needs 64-bit row addressing.  Skipped where the device is smaller."""
-    w = synth.WORKLOADS["rmc2-large"].with_batch(512)
+    case that needs 64-bit row addressing.  Skipped where the device is smaller.
+    B = 512 and B = 4096 (a point of the benchmark's latency sweep, all samples
+    checked) on one resident model."""
+    import gc
+    w0 = synth.WORKLOADS["rmc2-large"]
+    gc.collect()
+    torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
-    need = w.num_tables * w.rows * w.emb_dim * 2 + (8 << 30)
+    need = w0.num_tables * w0.rows * w0.emb_dim * 2 + (8 << 30)
     if free < need:
         pytest.skip(f"needs {need >> 30} GiB of device memory, {free >> 30} GiB free")
-    say("large-capacity workload, batch", w.batch)
-    m, bottom, top = H.make_workload_model(binding, w)
-    batch = synth.draw_batch(w, 0)
-    assert batch.indices.max() > (1 << 24)          # byte offsets beyond 2^31 are exercised
-    logits = H.run(m, batch)
-    assert m.check() == (binding.REC_OK, -1)
-    pick = np.array([0, 1, 255, 256, 510, 511])
-    exact = H.oracle_on_slice(w, batch, pick, bottom, top)
-    mirror = H.oracle_on_slice(w, batch, pick, bottom, top, orc.BF16_MIRROR)
-    pooled = m.debug_pooled()[torch.from_numpy(pick).cuda()].cpu().numpy()
-    H.check_pooled(pooled, exact["pooled"], exact["abs_sum"])
-    H.check_logits(logits[pick], exact["logits"], mirror["logits"])
+    m, bottom, top = H.make_workload_model(binding, w0, max_batch=4096)
+    cdf = synth.zipf_cdf(w0.rows, float(w0.index_dist[1]))
+    for B in (512, 4096):
+        w = w0.with_batch(B)
+        say("large-capacity workload, batch", w.batch)
+        batch = synth.draw_batch(w, 0, cdf)
+        assert batch.indices.max() > (1 << 24)          # byte offsets beyond 2^31 are exercised
+        logits = H.run(m, batch)
+        if B == 4096:
+            whole_batch_check(binding, m, w, batch, logits, bottom, top, w.name)
+            continue
+        assert m.check() == (binding.REC_OK, -1)
+        pick = np.array([0, 1, 255, 256, B - 2, B - 1])
+        exact = H.oracle_on_slice(w, batch, pick, bottom, top)
+        mirror = H.oracle_on_slice(w, batch, pick, bottom, top, orc.BF16_MIRROR)
+        pooled = m.debug_pooled()[torch.from_numpy(pick).cuda()].cpu().numpy()
+        H.check_pooled(pooled, exact["pooled"], exact["abs_sum"])
+        H.check_logits(logits[pick], exact["logits"], mirror["logits"])
     m.close()
+    del m
+    gc.collect()
     torch.cuda.empty_cache()
 
 

@@ -1,0 +1,151 @@
+"""The sparse-dense pipeline (REC_OPT_PIPELINE): scan and pooling of batch i + 1
+on the caller's stream beside Bottom-FC, interaction and Predict-FC of batch i
+on a second stream.  Same kernels as the in-order pass, so the logits must be
+bit-equal to it, and they are held to the oracle's bars as well.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rec_oracle as orc
+from paper_2203_07424_amd import synth
+
+import gpu_helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2203_07424_amd import binding as b
+    return b
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def dev(batch):
+    return (torch.from_numpy(batch.dense).cuda(), torch.from_numpy(batch.indices).cuda(),
+            torch.from_numpy(batch.lengths).cuda())
+
+
+@pytest.mark.parametrize("name,own_dense_stream", [("tiny", True), ("tiny", False), ("mtwnd-tiny", True)])
+def test_pipelined_forwards_equal_in_order_forwards(binding, name, own_dense_stream):
+    """Nine back-to-back forwards of varying batch size, no host synchronisation
+    in between, results read after rec_drain(): bit-equal to the in-order model
+    and within the bars against the oracle."""
+    w = synth.WORKLOADS[name]
+    say("pipeline vs in-order", name, own_dense_stream)
+    sizes = [w.batch, 37, w.batch, 1, 129, w.batch, 64, 3, w.batch]
+    ref, bottom, top = H.make_workload_model(binding, w)
+    main = torch.cuda.Stream()
+    side = torch.cuda.Stream() if own_dense_stream else None
+    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side)
+    tabs = [synth.full_table(w, t) for t in range(w.num_tables)]
+    batches = [synth.draw_batch(w.with_batch(B), 60 + i) for i, B in enumerate(sizes)]
+    data = [dev(b) for b in batches]
+    shape = lambda B: (B,) if w.towers == 1 else (B, w.towers)
+    want = []
+    for b, d in zip(batches, data):
+        want.append(ref.forward(*d).cpu().numpy())
+    torch.cuda.synchronize()
+    outs = [torch.full(shape(B), float("nan"), dtype=torch.float32, device="cuda") for B in sizes]
+    with torch.cuda.stream(main):
+        for d, o in zip(data, outs):
+            pm.forward(*d, o)
+        pm.drain()
+        got = [o.cpu() for o in outs]          # ordered on `main` behind the drain
+    main.synchronize()
+    assert pm.check() == (binding.REC_OK, -1) and ref.check() == (binding.REC_OK, -1)
+    for i, (g, wnt) in enumerate(zip(got, want)):
+        assert np.array_equal(g.numpy(), wnt), i
+    for i in (0, 1, 3, 8):
+        b = batches[i]
+        fwd = orc.forward_towers if w.interaction == "concat" else orc.forward
+        exact = fwd(b.dense, tabs, b.indices, b.lengths, bottom, top)
+        mirror = fwd(b.dense, tabs, b.indices, b.lengths, bottom, top, orc.BF16_MIRROR)
+        H.check_logits(got[i].numpy(), exact["logits"], mirror["logits"])
+    # the buffers of the last call's frame can be inspected once it is done
+    last = batches[-1]
+    assert np.array_equal(np.diff(pm.debug_offsets().cpu().numpy().astype(np.int64)), last.lengths)
+    pm.close()
+    ref.close()
+
+
+def test_pipelined_results_are_ordered_behind_the_next_call(binding):
+    """Without a drain the logits of call i are ordered on the caller's stream
+    behind call i + 1: a copy enqueued there sees them complete."""
+    w = synth.WORKLOADS["tiny"]
+    say("pipeline: ordering behind the next call")
+    ref, _, _ = H.make_workload_model(binding, w)
+    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True,
+                                     dense_stream=torch.cuda.Stream())
+    batches = [synth.draw_batch(w, 80 + i) for i in range(6)]
+    data = [dev(b) for b in batches]
+    want = [ref.forward(*d).cpu().numpy() for d in data]
+    main = torch.cuda.Stream()
+    outs = [torch.empty(w.batch, dtype=torch.float32, device="cuda") for _ in data]
+    snaps = []
+    with torch.cuda.stream(main):
+        for i, (d, o) in enumerate(zip(data, outs)):
+            pm.forward(*d, o)
+            if i > 0:
+                snaps.append(outs[i - 1].clone())       # enqueued on `main`, behind call i
+    main.synchronize()
+    for i, sn in enumerate(snaps):
+        assert np.array_equal(sn.cpu().numpy(), want[i]), i
+    assert pm.check() == (binding.REC_OK, -1)            # check() drains
+    assert np.array_equal(outs[-1].cpu().numpy(), want[-1])
+    # the option decides the workspace size: not changeable once one is bound
+    assert binding.rec_set_option(pm.handle, binding.REC_OPT_PIPELINE, 0) == binding.REC_ERR_STATE
+    pm.close()
+    ref.close()
+
+
+def test_pipelined_faults_are_reported(binding):
+    w = synth.WORKLOADS["tiny"].with_batch(64)
+    say("pipeline: device faults")
+    pm, _, _ = H.make_workload_model(binding, w, pipeline=True)
+    b = synth.draw_batch(w, 1)
+    bad = b.indices.copy()
+    bad[777] = -5
+    for idx, expect in ((bad, (binding.REC_ERR_INDEX_RANGE, 777)), (b.indices, (binding.REC_OK, -1))):
+        d, i, l = dev(synth.Batch(b.dense, idx, b.lengths))
+        out = pm.forward(d, i, l)
+        assert pm.check() == expect
+        assert torch.isfinite(out).all()
+    pm.close()
+
+
+def test_full_size_pipelined_whole_batches_against_oracle(binding):
+    """rmc2 at full size through the pipeline on two streams, four batches back
+    to back (the benchmark's launch configuration): every sample of the first
+    and the last batch against the oracle, all four bit-equal to in-order forwards."""
+    w = synth.WORKLOADS["rmc2"]
+    say("full-size pipelined", w.name)
+    ref, bottom, top = H.make_workload_model(binding, w)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side)
+    batches = [synth.draw_batch(w, 20 + i) for i in range(4)]
+    data = [dev(b) for b in batches]
+    want = [ref.forward(*d).cpu().numpy() for d in data]
+    outs = [torch.empty(w.batch, dtype=torch.float32, device="cuda") for _ in data]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(main):
+        for rep in range(3):
+            for d, o in zip(data, outs):
+                pm.forward(*d, o)
+        pm.drain()
+    main.synchronize()
+    assert pm.check() == (binding.REC_OK, -1)
+    for i in range(4):
+        assert np.array_equal(outs[i].cpu().numpy(), want[i]), i
+    for i in (0, 3):
+        exact, mirror, P, A = H.oracle_on_batch(w, batches[i], bottom, top)
+        H.check_logits(want[i], exact["logits"], mirror["logits"], mirror_rtol=1e-2)   # whole 4096-batch
+        if i == 3:      # the last call's frame
+            H.check_pooled(pm.debug_pooled().cpu().numpy(), P, A)
+    pm.close()
+    ref.close()
+    torch.cuda.empty_cache()

@@ -497,3 +497,22 @@ def test_towers_reject_bad_width_chain():
             (np.zeros((1, 3), np.float32), np.zeros(1, np.float32))]]
     with pytest.raises(ValueError):
         orc.forward_towers(dense, tabs, idx, lens, bot, bad)
+
+
+def test_bf16_mirror_per_sample_spread_against_exact_mode():
+    """What bf16 operands alone (no device) do to a logit: on a whole rmc1-style
+    batch the mirror stays within 2e-2 of the exact mode batch-wise, its median
+    per-sample deviation is a few 1e-3 of max(|o|, rms), and at most a sample or
+    two in a thousand cross 2e-2.  This is the spread the device is allowed."""
+    from paper_2203_07424_amd import synth
+    w = synth.WORKLOADS["rmc1"]
+    bottom, top = synth.draw_mlp(w, "bottom"), synth.draw_mlp(w, "top")
+    batch = synth.draw_batch(w, 0)
+    tabs, cidx = synth.compact_tables(w, batch, w.batch)
+    exact = orc.forward(batch.dense, tabs, cidx, batch.lengths, bottom, top)["logits"]
+    mirror = orc.forward(batch.dense, tabs, cidx, batch.lengths, bottom, top, orc.BF16_MIRROR)["logits"]
+    assert np.linalg.norm(mirror - exact) <= 2e-2 * np.linalg.norm(exact)
+    rms = np.sqrt((exact ** 2).mean())
+    ratio = np.abs(mirror - exact) / np.maximum(np.abs(exact), rms)
+    assert 5e-4 < np.median(ratio) < 1e-2
+    assert ratio.max() < 4e-2 and (ratio > 2e-2).sum() <= 3
