@@ -59,7 +59,8 @@ typedef enum {
     REC_ERR_LENGTHS = 4,     /* device: negative length, or sum(lengths) != nnz  */
     REC_ERR_INDEX_RANGE = 5, /* device: a row id outside [0, rows)               */
     REC_ERR_OVERFLOW = 6,    /* a count does not fit the 32-bit index math       */
-    REC_ERR_DEVICE = 7       /* a HIP call failed                                */
+    REC_ERR_DEVICE = 7,      /* a HIP call failed                                */
+    REC_ERR_CAPACITY = 8     /* rec_forward_static(): call exceeds the static scratch */
 } rec_status;
 
 typedef enum { REC_F32 = 0, REC_F16 = 1 } rec_dtype;
@@ -197,6 +198,32 @@ REC_API rec_status rec_load_mlp(rec_model *m, int32_t which, int32_t layer, cons
 REC_API rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_indices,
                        const int32_t *dev_lengths, int32_t batch, int64_t nnz,
                        float *dev_logits, void *stream);
+
+/*
+ * rec_forward() for callers that cannot allocate device memory or hand over a
+ * workspace of their own at call time: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same pass, same kernels,
+ * same results, but every intermediate (offsets, tile sums, pooled vectors,
+ * activations, table descriptors, error record) lives in a static device
+ * array of REC_STATIC_SCRATCH_BYTES that the library holds on each GPU it runs
+ * on until the process ends, laid out for `batch` (not max_batch) samples.
+ * The call allocates nothing and synchronises nothing; the bound workspace is
+ * not touched.  The model is set up as for rec_forward() (tables and layers
+ * registered); hot-row lists, REC_OPT_OVERLAP_DENSE, REC_OPT_PIPELINE and
+ * stage timing do not apply here.  The device of `stream` must be current.
+ *   dev_fault   device int64 [2], may be NULL: receives what rec_check() would
+ *               report for this call: [0] REC_OK / REC_ERR_LENGTHS /
+ *               REC_ERR_INDEX_RANGE, [1] the first bad position or -1.
+ * REC_ERR_CAPACITY if the model has more than REC_STATIC_MAX_TABLES tables or
+ * this batch needs more than REC_STATIC_SCRATCH_BYTES (nothing is enqueued);
+ * otherwise errors as rec_forward().  All calls on one GPU share the one
+ * array: calls that overlap on a GPU (two streams, two models) race.
+ */
+#define REC_STATIC_SCRATCH_BYTES (64u << 20)
+#define REC_STATIC_MAX_TABLES 64
+REC_API rec_status rec_forward_static(rec_model *m, const float *dev_dense, const int32_t *dev_indices,
+                              const int32_t *dev_lengths, int32_t batch, int64_t nnz,
+                              float *dev_logits, int64_t *dev_fault, void *stream);
 
 /* Waits for `stream` (and, pipelined, for the outstanding dense stages), reads
  * and clears the device error record.  Returns REC_OK,

@@ -26,7 +26,9 @@ _lib = C.CDLL(LIB_PATH)
 
 REC_OK = 0
 REC_ERR_ARG, REC_ERR_SHAPE, REC_ERR_STATE, REC_ERR_LENGTHS = 1, 2, 3, 4
-REC_ERR_INDEX_RANGE, REC_ERR_OVERFLOW, REC_ERR_DEVICE = 5, 6, 7
+REC_ERR_INDEX_RANGE, REC_ERR_OVERFLOW, REC_ERR_DEVICE, REC_ERR_CAPACITY = 5, 6, 7, 8
+REC_STATIC_SCRATCH_BYTES = 64 << 20
+REC_STATIC_MAX_TABLES = 64
 REC_F32, REC_F16 = 0, 1
 REC_BOTTOM, REC_TOP = 0, 1          # REC_TOP + k: tower k of the Predict-FC
 REC_INTERACT_DOT, REC_INTERACT_CONCAT = 0, 1
@@ -40,7 +42,7 @@ REC_NUM_STAGES = 6
 STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top_first", "top_rest")
 
 EXPORTS = ("rec_create", "rec_destroy", "rec_workspace_bytes", "rec_bind_workspace",
-           "rec_load_tables", "rec_load_hot_rows", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_check",
+           "rec_load_tables", "rec_load_hot_rows", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_forward_static", "rec_check",
            "rec_debug_get", "rec_set_option", "rec_set_dense_stream", "rec_drain", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
            "rec_synth_fill_table")
 
@@ -73,6 +75,8 @@ _lib.rec_load_mlp.restype = C.c_int
 _lib.rec_load_mlp.argtypes = [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp]
 _lib.rec_forward.restype = C.c_int
 _lib.rec_forward.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int64, _vp, _vp]
+_lib.rec_forward_static.restype = C.c_int
+_lib.rec_forward_static.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int64, _vp, _vp, _vp]
 _lib.rec_check.restype = C.c_int
 _lib.rec_check.argtypes = [_vp, _vp, C.POINTER(C.c_int64)]
 _lib.rec_debug_get.restype = C.c_int
@@ -164,6 +168,12 @@ def rec_load_mlp(m: int, which: int, layer: int, dev_W: torch.Tensor, dev_b: tor
 def rec_forward(m: int, dev_dense, dev_indices, dev_lengths, batch: int, nnz: int, dev_logits) -> int:
     return _lib.rec_forward(m, _ptr(dev_dense), _ptr(dev_indices), _ptr(dev_lengths), batch, nnz,
                             _ptr(dev_logits), _stream())
+
+
+def rec_forward_static(m: int, dev_dense, dev_indices, dev_lengths, batch: int, nnz: int, dev_logits,
+                       dev_fault=None) -> int:
+    return _lib.rec_forward_static(m, _ptr(dev_dense), _ptr(dev_indices), _ptr(dev_lengths), batch, nnz,
+                                   _ptr(dev_logits), _ptr(dev_fault), _stream())
 
 
 def rec_check(m: int) -> Tuple[int, int]:
@@ -296,6 +306,23 @@ class RecModel:
         self._ok(rec_forward(self.handle, dense, indices, lengths, batch, indices.numel(), logits),
                  "rec_forward")
         self.last_batch = batch
+        return logits
+
+    def forward_static(self, dense: torch.Tensor, indices: torch.Tensor, lengths: torch.Tensor,
+                       logits: torch.Tensor, fault: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """rec_forward_static(): the same pass with the library's static scratch; the
+        caller brings every buffer (logits fp32, fault int64 [2] or None)."""
+        batch = dense.shape[0]
+        for name, t, dt, n in (("dense", dense, torch.float32, batch * self.F),
+                               ("indices", indices, torch.int32, indices.numel()),
+                               ("lengths", lengths, torch.int32, self.T * batch),
+                               ("logits", logits, torch.float32, batch * self.towers)):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and t.numel() >= n):
+                raise ValueError(f"rec_forward_static: {name} must be a contiguous {dt} device tensor of at least {n} elements")
+        if fault is not None and not (fault.is_cuda and fault.dtype == torch.int64 and fault.numel() >= 2):
+            raise ValueError("rec_forward_static: fault must be an int64 device tensor of 2 elements")
+        self._ok(rec_forward_static(self.handle, dense, indices, lengths, batch, indices.numel(), logits, fault),
+                 "rec_forward_static")
         return logits
 
     def check(self) -> Tuple[int, int]:

@@ -5,12 +5,18 @@
 // Bottom-FC does not depend on the SparseNet and Predict-FC waits for both
 // (Sec. III-A); on one in-order stream that dependency is the launch order.
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "rec_internal.h"
 
 using namespace rec;
+
+// Scratch memory of rec_forward_static(): one copy per GPU the library runs on,
+// held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress(); kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[REC_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -401,6 +407,69 @@ hipError_t enqueue_in_order(const rec_model *m, const Bufs &u, const Call &c, bo
     return enqueue_tail(m, u, c, s, ev);
 }
 
+// Device address of `scratch` on each GPU, looked up once per device with that
+// device current.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mu;
+char *g_scratch_ptr[MAX_DEVICES] = {};
+
+rec_status static_scratch(char **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return REC_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return REC_ERR_DEVICE;
+        if (fc_big_prepare() != hipSuccess || chain_prepare() != hipSuccess) return REC_ERR_DEVICE;
+        g_scratch_ptr[dev] = static_cast<char *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return REC_OK;
+}
+
+// Table descriptors by value: what rec_forward_static() writes into its scratch
+// at the start of every call.
+struct StaticTables {
+    const void *base[REC_STATIC_MAX_TABLES];
+    long long rows[REC_STATIC_MAX_TABLES];
+};
+
+__global__ __launch_bounds__(64) void static_begin_kernel(const StaticTables st, int T, TableDesc *dst,
+                                                          ErrRecord *err)
+{
+    const int t = threadIdx.x;
+    if (t < T) {
+        dst[t].base = st.base[t];
+        dst[t].rows = st.rows[t];
+        dst[t].hot_ids = nullptr;
+        dst[t].n_hot = 0;
+        dst[t].pad = 0;
+    }
+    if (t == 0) {
+        err->first_bad_len = ~0ull;
+        err->first_bad_idx = ~0ull;
+        err->flags = 0u;
+    }
+}
+
+// fault[0] = the status rec_check() would give for this call, fault[1] = its position.
+__global__ __launch_bounds__(64) void static_end_kernel(const ErrRecord *err, long long *fault)
+{
+    if (threadIdx.x != 0) return;
+    const unsigned flags = err->flags;
+    long long st = REC_OK, pos = -1;
+    if (flags & (ERR_NEG_LENGTH | ERR_TOTAL_MISMATCH)) {
+        st = REC_ERR_LENGTHS;
+        if (flags & ERR_NEG_LENGTH) pos = (long long)err->first_bad_len;
+    } else if (flags & ERR_INDEX_RANGE) {
+        st = REC_ERR_INDEX_RANGE;
+        pos = (long long)err->first_bad_idx;
+    }
+    fault[0] = st;
+    fault[1] = pos;
+}
+
 // Host-checkable faults of a forward call.
 rec_status check_call(const rec_model *m, const float *dev_dense, const int32_t *dev_indices,
                       const int32_t *dev_lengths, int32_t batch, int64_t nnz, const float *dev_logits)
@@ -430,6 +499,7 @@ const char *rec_status_string(int status)
     case REC_ERR_INDEX_RANGE: return "row id outside its table";
     case REC_ERR_OVERFLOW: return "count exceeds 32-bit index range";
     case REC_ERR_DEVICE: return "HIP call failed";
+    case REC_ERR_CAPACITY: return "call needs more scratch than the static array holds";
     }
     return "unknown status";
 }
@@ -549,6 +619,10 @@ rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *s
     m->tail_pending[0] = m->tail_pending[1] = false;
     m->next_frame = m->last_frame = 0;
     if (fc_big_prepare() != hipSuccess || chain_prepare() != hipSuccess) return REC_ERR_DEVICE;
+    {   // set-up is also where the static scratch of this device is looked up
+        char *unused = nullptr;
+        if (static_scratch(&unused) != REC_OK) return REC_ERR_DEVICE;
+    }
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
@@ -701,6 +775,43 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
     }
 #undef REC_DEV
     if (m->slots > 0) ++m->forwards;
+    return REC_OK;
+}
+
+rec_status rec_forward_static(rec_model *m, const float *dev_dense, const int32_t *dev_indices,
+                              const int32_t *dev_lengths, int32_t batch, int64_t nnz, float *dev_logits,
+                              int64_t *dev_fault, void *stream)
+{
+    const rec_status st = check_call(m, dev_dense, dev_indices, dev_lengths, batch, nnz, dev_logits);
+    if (st != REC_OK) return st;
+    if (m->T > REC_STATIC_MAX_TABLES) return REC_ERR_CAPACITY;
+    const Carve lay = carve(m, batch > 0 ? batch : 1, 1);
+    if (lay.bytes > REC_STATIC_SCRATCH_BYTES) return REC_ERR_CAPACITY;
+    char *base = nullptr;
+    const rec_status sp = static_scratch(&base);
+    if (sp != REC_OK) return sp;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Bufs u = bufs_at(base, lay, 0);
+    // The array keeps what the last call left: descriptors and error record are
+    // written afresh; every other part is fully overwritten before it is read.
+    StaticTables tabs{};
+    for (int t = 0; t < m->T; ++t) {
+        tabs.base[t] = m->desc[t].base;
+        tabs.rows[t] = m->desc[t].rows;
+    }
+    hipLaunchKernelGGL(static_begin_kernel, dim3(1), dim3(64), 0, s, tabs, m->T,
+                       const_cast<TableDesc *>(u.tables), u.err);
+    if (hipGetLastError() != hipSuccess) return REC_ERR_DEVICE;
+    if (batch > 0) {
+        const Call c{dev_dense, dev_indices, dev_lengths, batch, nnz, dev_logits};
+        if (enqueue_in_order(m, u, c, false, s, nullptr) != hipSuccess) return REC_ERR_DEVICE;
+    }
+    if (dev_fault) {
+        hipLaunchKernelGGL(static_end_kernel, dim3(1), dim3(64), 0, s, u.err,
+                           reinterpret_cast<long long *>(dev_fault));
+        if (hipGetLastError() != hipSuccess) return REC_ERR_DEVICE;
+    }
     return REC_OK;
 }
 
