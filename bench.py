@@ -4,22 +4,34 @@
 One step = one rec_forward() over one synthetic batch: offsets scan, embedding
 bag pooling, Bottom-FC, pairwise-dot interaction, Predict-FC.  Inputs and
 tables are resident in HBM before the timed region.  Prints ONE JSON line.
-The default workload (rmc2) is bound by the pooling kernel and its roofline is
-HBM bandwidth; --workload mtwnd (one lookup per table, concatenation, four
-Predict-FC towers) is bound by its first tower layer and reports that GEMM
-against the bf16 MFMA peak.
 
-The timed region runs one model instance on one stream.  --instances N
-co-locates N instances (own stream and workspace each, tables shared) which
-take the K steps in turn; the default run also reports such a leg, measured
-after the timed region, under "co_located".
+Default run (workload rmc2, the configuration the metric is quoted on):
+  value               K steps through the pipelined model (pooling launches back to
+                      back on one stream, the dense stages of the neighbouring
+                      batches beside them on a second one), drained and synchronised
+  in_order            the same K steps with everything in order on one stream
+  sustained           the pipelined loop kept up for at least two seconds
+  latency_ms          one batch at a time, host launch and synchronisation included
+  stage_ms, mlp_mfma  HIP-event brackets around every stage of in-order forwards
+  roofline            the pooling kernel on the uniform-id twin (no reuse for the
+                      caches to serve): algorithmic bytes / launch time against the
+                      HBM peak
+  roofline_zipf       the same kernel on the headline's skewed ids, where the caches
+                      serve most rows: algorithmic rate, and the bytes that must come
+                      from HBM at least (unique rows + ids) against the peak
+  co_located          two in-order instances sharing the tables, a stream each
+  other_workloads     short legs of tiny, rmc1, rmc3, mtwnd and the batch-size sweep
+                      of rmc2-large (154 GB resident) with its latency-bounded rate
+  cpu_baseline        the CPU oracle, as it stands, on a bounded sample
 
-  python bench.py [--steps K] [--warmup W] [--workload rmc2] [--uniform] [--instances N]
+  python bench.py [--steps K] [--warmup W] [--workload rmc2] [--uniform]
   python bench.py --workload rmc2-large --latency-sweep
+  python bench.py --search
 """
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -35,8 +47,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 # HBM traffic of one pooling launch from rocprofv3 counter runs (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what it reads for a plain 1 GiB copy: 2.000 and
 # 1.000), see profiles/pool_rmc2_counters.md; Zipf ids with cached row loads,
-# the uniform twin with non-temporal ones (what --stream-rows auto picks).  Valid only for the kernel source
-# the counters were taken with; reported as null once csrc/pool.hip differs.
+# the uniform twin with non-temporal ones.  These are figures from a profile, not
+# of this run, and hold only for the kernel source the counters were taken with:
+# reported as null once csrc/pool.hip differs.
 POOL_TRAFFIC = {
     "sha256": "ab1846d96d7f5f0750d6a6ca9f670f1d5e0548b462a4c702c976c977754e84da",
     ("rmc2", 4096): {"fetch_bytes": 553907362.0, "write_bytes": 41943050.0},
@@ -44,7 +57,7 @@ POOL_TRAFFIC = {
 }
 
 
-def measured_pool_traffic(w, streaming):
+def profiled_pool_traffic(w, streaming):
     import hashlib
     if streaming != (w.index_dist[0] == "uniform"):   # the counters were taken with the automatic choice
         return None
@@ -62,13 +75,44 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def dtype_string(w) -> str:
+    tab = "f16" if w.table_dtype == "f16" else "f32"
+    s = f"{tab} tables -> f32 pooling sums; bf16 MFMA -> f32 accumulate (FC layers)"
+    if w.interaction == "dot":
+        s += "; interaction: f32 operands split into two bf16 planes on bf16 MFMA (16 significant bits) -> bf16"
+    return s
+
+
+def workload_string(w) -> str:
+    return (f"{w.name}: {w.num_tables} tables x {w.rows} rows x dim {w.emb_dim} {w.table_dtype}, "
+            f"pooling {w.pooling}, ids {w.index_dist}, bottom {list(w.bottom)}, top {list(w.top)}"
+            + (f" x {w.towers} towers, concatenation" if w.interaction == "concat" else ""))
+
+
 def algorithmic_pool_bytes(w, batch) -> int:
     """Bytes the pooling launch must move: gathered rows, their ids, the bag
-    offsets, and the pooled vectors it writes."""
+    offsets, and the pooled vectors it writes (counted: yes)."""
     elt = 2 if w.table_dtype == "f16" else 4
     bags = w.num_tables * w.batch
+    out_elt = 2 if w.interaction == "concat" else 4
     return (batch.nnz * w.emb_dim * elt + batch.nnz * 4 + (bags + 1) * 4
-            + bags * w.emb_dim * 4)
+            + bags * w.emb_dim * out_elt)
+
+
+def compulsory_pool_bytes(w, batch) -> int:
+    """Bytes that must come from or go to HBM at least: every distinct row once,
+    the ids, the offsets and the pooled vectors."""
+    import numpy as np
+    elt = 2 if w.table_dtype == "f16" else 4
+    bags = w.num_tables * w.batch
+    per_table = batch.lengths.reshape(w.num_tables, w.batch).sum(axis=1, dtype=np.int64)
+    pos, uniq = 0, 0
+    for t in range(w.num_tables):
+        n = int(per_table[t])
+        uniq += np.unique(batch.indices[pos:pos + n]).size
+        pos += n
+    out_elt = 2 if w.interaction == "concat" else 4
+    return uniq * w.emb_dim * elt + batch.nnz * 4 + (bags + 1) * 4 + bags * w.emb_dim * out_elt
 
 
 def cpu_baseline(w, batches, bottom, top, n_samples: int) -> dict:
@@ -82,7 +126,7 @@ def cpu_baseline(w, batches, bottom, top, n_samples: int) -> dict:
     threads = orc.set_threads(cores)
     dt = 0.0
     for batch in batches:
-        sub = synth.slice_samples(w, batch, np.arange(n_samples))
+        sub = synth.slice_samples(w, batch, np.arange(n_samples)) if n_samples < w.batch else batch
         tabs, cidx = synth.compact_tables(w, sub, n_samples)
         t0 = time.perf_counter()
         if w.interaction == "concat":
@@ -113,7 +157,7 @@ def cpu_baseline(w, batches, bottom, top, n_samples: int) -> dict:
 FUSE_MLP = "auto"   # --fuse-mlp: how runs of narrow FC layers are launched
 
 
-def build_model(binding, synth, torch, w, max_batch, share_tables=None):
+def build_model(binding, synth, torch, w, max_batch, share_tables=None, pipeline=False, dense_stream=None):
     """Model of workload `w` with tables filled on the device (or shared with
     the model `share_tables`) and packed MLPs."""
     dev = torch.device("cuda:0")
@@ -121,7 +165,8 @@ def build_model(binding, synth, torch, w, max_batch, share_tables=None):
     m = binding.RecModel(w.num_tables, w.emb_dim, [w.rows] * w.num_tables, w.table_dtype,
                          w.num_dense, list(w.bottom), list(w.top), max_batch,
                          min(max_batch * w.num_tables * hi, 2 ** 31 - 1),
-                         interaction=w.interaction, towers=w.towers)
+                         interaction=w.interaction, towers=w.towers, pipeline=pipeline,
+                         dense_stream=dense_stream)
     tdt = torch.float16 if w.table_dtype == "f16" else torch.float32
     for t in range(w.num_tables):
         if share_tables is not None:
@@ -184,10 +229,183 @@ def pick_concurrent_streams(torch, dev, n):
     return chosen
 
 
+def make_batches(torch, synth, wl, n, first_id, dev, workers=8):
+    """n distinct batches of workload wl: host copies and device-resident tensors."""
+    from concurrent.futures import ThreadPoolExecutor
+    cdf = synth.zipf_cdf(wl.rows, float(wl.index_dist[1])) if wl.index_dist[0] == "zipf" else None
+    if n >= workers:
+        with ThreadPoolExecutor(workers) as ex:
+            hb = list(ex.map(lambda i: synth.draw_batch(wl, first_id + i, cdf), range(n)))
+    else:
+        hb = [synth.draw_batch(wl, first_id + i, cdf, workers=workers) for i in range(n)]
+    db = [(torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
+           torch.from_numpy(b.lengths).to(dev)) for b in hb]
+    torch.cuda.synchronize()
+    return hb, db
+
+
+def run_steps(torch, model, stream, db, outs, steps, first=0):
+    """steps forwards of `model` on `stream` over the batches in turn, drained
+    and synchronised; returns seconds."""
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    with torch.cuda.stream(stream):
+        for i in range(first, first + steps):
+            model.forward(*db[i % len(db)], outs[i % len(outs)])
+        model.drain()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t
+
+
+def stage_profile(torch, binding, np, model, stream, db, n):
+    """n in-order forwards, every stage bracketed with HIP events on `stream`.
+    Returns (mean ms per stage, per-forward pool ms, index of the batch each used)."""
+    with torch.cuda.stream(stream):
+        for i in range(5):
+            model.forward(*db[i % len(db)])
+        model.drain()
+        torch.cuda.synchronize()
+        model.set_profiling(n, 1)
+        outs = [None] * len(db)
+        for i in range(n):
+            outs[i % len(db)] = model.forward(*db[i % len(db)], outs[i % len(db)])
+        model.drain()
+    torch.cuda.synchronize()
+    rows = np.array([list(model.stage_ms(j).values()) for j in range(n)])
+    model.set_profiling(0)
+    mean = dict(zip(binding.STAGE_NAMES, rows.mean(axis=0).tolist()))
+    return mean, rows[:, binding.STAGE_NAMES.index("pool")], [i % len(db) for i in range(n)]
+
+
+def latency_profile(torch, np, model, stream, db, out, iters, warmup=10):
+    """One batch in flight at a time: per-batch latency, host launch and synchronisation included."""
+    with torch.cuda.stream(stream):
+        for i in range(warmup):
+            model.forward(*db[i % len(db)], out)
+        model.drain()
+        torch.cuda.synchronize()
+        lat = np.empty(iters)
+        for i in range(iters):
+            t = time.perf_counter()
+            model.forward(*db[i % len(db)], out)
+            model.drain()
+            stream.synchronize()
+            lat[i] = time.perf_counter() - t
+    return {"p50": float(np.percentile(lat, 50) * 1e3), "p99": float(np.percentile(lat, 99) * 1e3),
+            "min": float(lat.min() * 1e3), "max": float(lat.max() * 1e3), "mean": float(lat.mean() * 1e3),
+            "iterations": iters}
+
+
+def mlp_mfma(wl, avg):
+    """Matrix-unit use of the FC stages: unpadded 2*M*N*K of the stage's layers over
+    its HIP-event interval (which includes one event record and, for small
+    layers, mostly launch latency) against the bf16 MFMA peak.  bottom_first and
+    top_first bracket a single launch each."""
+    def flops(widths):
+        return sum(2.0 * wl.batch * widths[i] * widths[i + 1] for i in range(len(widths) - 1))
+    out = {}
+    for stage, widths, mult in (("bottom_first", wl.bottom[:2], 1), ("bottom_rest", wl.bottom[1:], 1),
+                                ("top_first", wl.top[:2], wl.towers), ("top_rest", wl.top[1:], wl.towers)):
+        f = flops(widths) * mult
+        if f > 0 and avg.get(stage, 0) > 0:
+            tf = f / (avg[stage] * 1e-3) / 1e12
+            out[stage] = {"gflop": f / 1e9, "ms": avg[stage], "tflops": tf,
+                          "frac_of_bf16_peak": tf / MFMA_BF16_PEAK_TFLOPS}
+    return out
+
+
+def pool_roofline(np, wl, hb, used, pool_ms, streaming, kind="algorithmic"):
+    """The pooling kernel against the HBM peak: bytes per launch over the mean
+    launch time of the timed launches."""
+    fn = algorithmic_pool_bytes if kind == "algorithmic" else compulsory_pool_bytes
+    per_batch = [fn(wl, b) for b in hb]
+    nbytes = float(np.mean([per_batch[i] for i in used]))
+    ms = float(np.mean(pool_ms))
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    return {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm", "achieved": gbps,
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS,
+            "traffic": profiled_pool_traffic(wl, streaming), "bytes_per_launch": nbytes,
+            "bytes_counted": "gathered rows + ids + offsets + pooled vectors written" if kind == "algorithmic"
+                             else "distinct rows + ids + offsets + pooled vectors written",
+            "avg_launch_ms": ms, "min_launch_ms": float(np.min(pool_ms)), "launches_timed": int(len(pool_ms)),
+            "distinct_batches": len(hb), "workload": wl.name,
+            "row_loads": "non-temporal" if streaming else "cached"}
+
+
+def short_leg(torch, binding, synth, np, name, args, dev, streams):
+    """One of the other workloads: throughput in order and pipelined, per-batch
+    latency, stage times, matrix-unit use of its FC stages, pooling rate."""
+    w = synth.WORKLOADS[name]
+    t0 = time.time()
+    m, _, _ = build_model(binding, synth, torch, w, w.batch)
+    pm, _, _ = build_model(binding, synth, torch, w, w.batch, share_tables=m, pipeline=True,
+                           dense_stream=streams[1])
+    streaming = w.index_dist[0] == "uniform"
+    for mm in (m, pm):
+        mm.set_option(binding.REC_OPT_STREAM_ROWS, int(streaming))
+    hb, db = make_batches(torch, synth, w, 8, 0, dev)
+    outs = [new_logits(torch, w, w.batch, dev) for _ in range(4)]
+    steps = args.other_steps
+    res = {"workload": workload_string(w), "batch": w.batch, "dtype": dtype_string(w), "steps": steps,
+           "distinct_batches": len(hb)}
+    for label, model in (("in_order", m), ("pipelined", pm)):
+        run_steps(torch, model, streams[0], db, outs, 20)
+        dt = run_steps(torch, model, streams[0], db, outs, steps)
+        res[label] = {"value": w.batch * steps / dt, "unit": "samples/s", "ms_per_step": dt * 1e3 / steps}
+        assert model.check() == (binding.REC_OK, -1)
+    res["value"] = max(res["in_order"]["value"], res["pipelined"]["value"])
+    res["latency_ms"] = latency_profile(torch, np, m, streams[0], db, outs[0], 100)
+    avg, pool_ms, used = stage_profile(torch, binding, np, m, streams[0], db, 32)
+    res["stage_ms"] = avg
+    res["mlp_mfma"] = mlp_mfma(w, avg)
+    res["pooling"] = pool_roofline(np, w, hb, used, pool_ms, streaming)
+    if w.index_dist[0] == "zipf":      # cache-served: an algorithmic rate, not a fraction of the HBM peak
+        res["pooling"]["algorithmic_gbps"] = res["pooling"].pop("achieved")
+        for k in ("frac", "bound"):
+            res["pooling"].pop(k)
+    m.close()
+    pm.close()
+    log(f"  {name}: {res['value'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
+    return res
+
+
+def sweep_leg(torch, binding, synth, np, w0, sizes, iters, sla_ms, dev, stream, warmup=10):
+    """Batch-size sweep: per-batch latency, one batch in flight (closed loop: queuing
+    delay excluded), and the latency-bounded throughput (Sec. II-B) under sla_ms."""
+    t0 = time.time()
+    m, _, _ = build_model(binding, synth, torch, w0, max(sizes))
+    log(f"  {w0.name} resident ({time.time() - t0:.1f} s)")
+    rows = []
+    for B in sizes:
+        w = w0.with_batch(B)
+        hb, db = make_batches(torch, synth, w, 2, 1000, dev)
+        out = new_logits(torch, w, B, dev)
+        lat = latency_profile(torch, np, m, stream, db, out, iters, warmup)
+        assert m.check() == (binding.REC_OK, -1)
+        rows.append({"batch": B, "mean_nnz": float(np.mean([b.nnz for b in hb])), "p50_ms": lat["p50"],
+                     "p99_ms": lat["p99"], "max_ms": lat["max"], "samples_per_s": B / (lat["mean"] * 1e-3)})
+        log(f"  B={B}: p50 {lat['p50']:.3f} ms p99 {lat['p99']:.3f} ms "
+            f"{rows[-1]['samples_per_s'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
+        del db, out
+    m.close()
+
+    def bounded(limit):
+        ok = [r for r in rows if r["p99_ms"] <= limit]
+        return max(ok, key=lambda r: r["samples_per_s"]) if ok else None
+    best, best50 = bounded(sla_ms), bounded(50.0)
+    return {"workload": workload_string(w0), "dtype": dtype_string(w0), "sla_ms": sla_ms,
+            "latency_bounded_samples_per_s": best["samples_per_s"] if best else None,
+            "best_batch": best["batch"] if best else None,
+            "at_the_paper_s_50_ms_bound": {"samples_per_s": best50["samples_per_s"] if best50 else None,
+                                           "best_batch": best50["batch"] if best50 else None},
+            "iterations_per_batch_size": iters,
+            "note": "closed loop, one batch in flight; per-batch latency includes the host's launch calls; "
+                    "queuing delay excluded; p99 over the timed iterations",
+            "sweep": rows}
+
+
 def latency_sweep(args) -> int:
-    """Per-batch latency over a batch-size sweep and the latency-bounded
-    throughput (Sec. II-B: throughput under an SLA tail-latency target).
-    Closed loop, one batch in flight, so queuing delay is not included."""
+    """--latency-sweep: the sweep alone, as the JSON line's subject."""
     import numpy as np
     import torch
     from paper_2203_07424_amd import binding, synth
@@ -196,53 +414,18 @@ def latency_sweep(args) -> int:
     sizes = [int(x) for x in args.sweep_batches.split(",")]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    t0 = time.time()
-    m, _, _ = build_model(binding, synth, torch, w0, max(sizes))
-    log(f"model {w0.name} resident ({time.time() - t0:.1f} s)")
-    cdf = synth.zipf_cdf(w0.rows, float(w0.index_dist[1])) if w0.index_dist[0] == "zipf" else None
-    rows = []
-    for B in sizes:
-        w = w0.with_batch(B)
-        hb = [synth.draw_batch(w, 1000 + i, cdf) for i in range(2)]
-        db = [(torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
-               torch.from_numpy(b.lengths).to(dev)) for b in hb]
-        logits = new_logits(torch, w, B, dev)
-        for i in range(args.warmup):
-            m.forward(*db[i % 2], logits)
-        torch.cuda.synchronize()
-        lat = np.empty(args.sweep_iters)
-        for i in range(args.sweep_iters):
-            t = time.perf_counter()
-            m.forward(*db[i % 2], logits)
-            torch.cuda.synchronize()
-            lat[i] = time.perf_counter() - t
-        st, pos = m.check()
-        assert st == binding.REC_OK, (st, pos)
-        rows.append({"batch": B, "mean_nnz": float(np.mean([b.nnz for b in hb])),
-                     "p50_ms": float(np.percentile(lat, 50) * 1e3),
-                     "p99_ms": float(np.percentile(lat, 99) * 1e3),
-                     "max_ms": float(lat.max() * 1e3),
-                     "samples_per_s": float(B / lat.mean())})
-        log(f"B={B}: p50 {rows[-1]['p50_ms']:.3f} ms p99 {rows[-1]['p99_ms']:.3f} ms "
-            f"{rows[-1]['samples_per_s'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
-        del db, logits
-    ok = [r for r in rows if r["p99_ms"] <= args.sla_ms]
-    best = max(ok, key=lambda r: r["samples_per_s"]) if ok else None
+    r = sweep_leg(torch, binding, synth, np, w0, sizes, args.sweep_iters, args.sla_ms, dev,
+                  torch.cuda.Stream(), args.warmup)
+    best = next((x for x in r["sweep"] if x["batch"] == r["best_batch"]), None)
     out = {"metric": f"latency-bounded samples/s per GPU at p99 <= {args.sla_ms} ms per batch",
-           "value": best["samples_per_s"] if best else None, "unit": "samples/s", "n_gpus": 1,
+           "value": r["latency_bounded_samples_per_s"], "unit": "samples/s", "n_gpus": 1,
            "steps": args.sweep_iters, "warmup": args.warmup,
            "ms_per_step": best["p50_ms"] if best else None, "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None,
-           "dtype": "f16 tables -> f32 accumulate; bf16 MFMA -> f32 accumulate",
-           "data": "synthetic",
-           "config": {"workload": f"{w0.name}: {w0.num_tables} tables x {w0.rows} rows x dim "
-                                  f"{w0.emb_dim} {w0.table_dtype}, ids {w0.index_dist}",
-                      "best_batch": best["batch"] if best else None, "sla_ms": args.sla_ms,
-                      "note": "closed loop, one batch in flight; per-batch latency includes the "
-                              "host's launch calls; queuing delay excluded"},
-           "sweep": rows}
+           "scaling": "weak", "vs_baseline": None, "dtype": dtype_string(w0), "data": "synthetic",
+           "config": {"workload": r["workload"], "best_batch": r["best_batch"], "sla_ms": args.sla_ms,
+                      "note": r["note"]},
+           "at_the_paper_s_50_ms_bound": r["at_the_paper_s_50_ms_bound"], "sweep": r["sweep"]}
     print(json.dumps(out), flush=True)
-    m.close()
     return 0
 
 
@@ -263,16 +446,12 @@ def search_mode(args) -> int:
     models = [m0] + [build_model(binding, synth, torch, w0, max(sizes), share_tables=m0)[0]
                      for _ in counts[1:]]
     streams = pick_concurrent_streams(torch, dev, len(counts))
-    cdf = synth.zipf_cdf(w0.rows, float(w0.index_dist[1])) if w0.index_dist[0] == "zipf" else None
     data = {}
     for B in sizes:
         w = w0.with_batch(B)
         outs = [new_logits(torch, w, B, dev) for _ in counts]
-        data[B] = []
-        for i in range(2):
-            b = synth.draw_batch(w, 2000 + i, cdf)
-            data[B].append((torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
-                            torch.from_numpy(b.lengths).to(dev), outs))
+        _, db = make_batches(torch, synth, w, 2, 2000, dev)
+        data[B] = [(d, i, l, outs) for d, i, l in db]
     log(f"{len(counts)} instances of {w0.name}, batches {sizes} resident ({time.time() - t0:.1f} s)")
     memo = {}
 
@@ -293,7 +472,7 @@ def search_mode(args) -> int:
            "steps": args.sweep_iters, "warmup": 8,
            "ms_per_step": res.measurement.latency_ms if res.measurement else None,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "f16 tables -> f32 accumulate; bf16 MFMA -> f32 accumulate", "data": "synthetic",
+           "dtype": dtype_string(w0), "data": "synthetic",
            "config": {"workload": w0.name, "instances": res.instances, "batch": res.batch,
                       "sla_ms": args.sla_ms, "points_measured_by_search": res.evaluated,
                       "grid_points": len(counts) * len(sizes)},
@@ -312,16 +491,20 @@ def main() -> int:
     ap.add_argument("--workload", default="rmc2")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--uniform", action="store_true", help="uniform ids instead of Zipf")
-    ap.add_argument("--batches", type=int, default=4, help="distinct input batches cycled")
-    ap.add_argument("--instances", type=int, default=1,
-                    help="co-located model instances in the timed region, each on its own "
-                         "stream, sharing the tables")
+    ap.add_argument("--batches", type=int, default=8, help="distinct input batches cycled")
+    ap.add_argument("--mode", choices=["pipelined", "in-order"], default="pipelined",
+                    help="what the timed region runs: the sparse-dense pipeline over two streams, "
+                         "or everything in order on one stream")
     ap.add_argument("--colocated-leg", type=int, default=2,
-                    help="instances of the extra co-located leg run after the timed region "
-                         "(0 or 1 = none)")
-    ap.add_argument("--extra-steps", type=int, default=30,
-                    help="steps of each extra single-instance leg (0 = none)")
+                    help="instances of the co-located leg (0 or 1 = none)")
+    ap.add_argument("--timed-launches", type=int, default=40,
+                    help="forwards whose stages are bracketed with HIP events, per leg")
+    ap.add_argument("--latency-iters", type=int, default=200)
+    ap.add_argument("--sustain-seconds", type=float, default=2.0)
+    ap.add_argument("--other-steps", type=int, default=200, help="steps of each other workload's leg")
+    ap.add_argument("--no-other-workloads", action="store_true")
     ap.add_argument("--cpu-samples", type=int, default=4096)
+    ap.add_argument("--cpu-batches", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (a kernel of known "
@@ -330,19 +513,13 @@ def main() -> int:
                     help="register the N most frequent rows of each table (profiled on two "
                          "batches that are not timed) so that pooling serves them from LDS")
     ap.add_argument("--graph", action="store_true",
-                    help="record the distinct batches' forwards into one HIP graph and replay "
-                         "it (steps are rounded to whole replays; no stage events)")
+                    help="record the distinct batches' in-order forwards into one HIP graph and replay "
+                         "it (steps are rounded to whole replays)")
     ap.add_argument("--stream-rows", choices=["auto", "on", "off"], default="auto",
                     help="pooling loads table rows with the non-temporal hint; auto = only for "
                          "workloads whose ids are drawn uniformly (no reuse for the caches to serve)")
     ap.add_argument("--fuse-mlp", choices=["auto", "on", "off"], default="auto",
                     help="runs of narrow FC layers as one kernel: the library's choice, always, never")
-    ap.add_argument("--overlap", action="store_true",
-                    help="run Bottom-FC on the library's side stream beside scan and pooling")
-    ap.add_argument("--event-period", type=int, default=10,
-                    help="bracket the stages of every N-th timed step with HIP events")
-    ap.add_argument("--no-stage-events", action="store_true",
-                    help="do not bracket stages with events inside the timed region")
     ap.add_argument("--latency-sweep", action="store_true",
                     help="batch-size sweep with per-batch latency percentiles instead of the "
                          "throughput run (meant for --workload rmc2-large)")
@@ -377,69 +554,27 @@ def main() -> int:
         w = w.with_uniform_indices()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    n_inst = max(1, args.instances)
-
     t0 = time.time()
-    m, bottom, top = build_model(binding, synth, torch, w, w.batch)
-    # Co-located instances (Sec. II-B, model co-location on the accelerator): each
-    # has its own workspace and stream; tables are shared, not copied.
-    models = [m] + [build_model(binding, synth, torch, w, w.batch, share_tables=m)[0]
-                    for _ in range(n_inst - 1)]
-    if args.overlap:
-        for mm in models:
-            mm.set_option(binding.REC_OPT_OVERLAP_DENSE, 1)
+    streams = pick_concurrent_streams(torch, dev, 2)
 
     def wants_streaming(wl):
         return args.stream_rows == "on" or (args.stream_rows == "auto" and wl.index_dist[0] == "uniform")
-    for mm in models:
+
+    m, bottom, top = build_model(binding, synth, torch, w, w.batch)
+    pm, _, _ = build_model(binding, synth, torch, w, w.batch, share_tables=m, pipeline=True,
+                           dense_stream=streams[1])
+    for mm in (m, pm):
         mm.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(w)))
     if args.hot_rows > 0:
         pcdf = synth.zipf_cdf(w.rows, float(w.index_dist[1])) if w.index_dist[0] == "zipf" else None
         hot = synth.profile_hot_rows(w, [900, 901], args.hot_rows, pcdf)
-        for mm in models:
+        for mm in (m, pm):
             for t in range(w.num_tables):
                 mm.load_hot_rows(t, hot[t])
-        log(f"hot rows: {args.hot_rows} per table from profiling batches 900, 901 ({time.time() - t0:.1f} s)")
-    streams = pick_concurrent_streams(torch, dev, n_inst)
-    torch.cuda.synchronize()
-    log(f"model {w.name}: {w.num_tables} x {w.rows} x {w.emb_dim} {w.table_dtype} resident, "
-        f"{n_inst} instance(s) ({time.time() - t0:.1f} s)")
-
-    def make_batches(wl, n, first_id):
-        cdf = synth.zipf_cdf(wl.rows, float(wl.index_dist[1])) if wl.index_dist[0] == "zipf" else None
-        hb = [synth.draw_batch(wl, first_id + i, cdf) for i in range(n)]
-        db = [(torch.from_numpy(b.dense).to(dev), torch.from_numpy(b.indices).to(dev),
-               torch.from_numpy(b.lengths).to(dev)) for b in hb]
-        return hb, db
-
-    host_batches, dev_batches = make_batches(w, args.batches, 0)
-    logits = [new_logits(torch, w, w.batch, dev) for _ in range(n_inst)]
-    torch.cuda.synchronize()
-    log(f"{args.batches} batches of {w.batch} resident, nnz[0] = {host_batches[0].nnz} "
-        f"({time.time() - t0:.1f} s)")
-
-    def step(i):
-        k = i % n_inst
-        d, idx, lens = dev_batches[i % len(dev_batches)]
-        with torch.cuda.stream(streams[k]):
-            models[k].forward(d, idx, lens, logits[k])
-
-    if args.graph:
-        # One replay = one forward over each distinct batch, single instance.
-        assert n_inst == 1
-        per = len(dev_batches)
-        glog = [new_logits(torch, w, w.batch, dev) for _ in range(per)]
-        with torch.cuda.stream(streams[0]):
-            cap = binding.CapturedForward(m, dev_batches, glog)
-        args.steps = max(per, args.steps // per * per)
-        args.no_stage_events = True
-        args.colocated_leg = 0
-        args.extra_steps = 0
-
-        def step(i):                                    # noqa: F811
-            if i % per == 0:
-                with torch.cuda.stream(streams[0]):
-                    cap.replay()
+    log(f"model {w.name}: {w.num_tables} x {w.rows} x {w.emb_dim} {w.table_dtype} resident ({time.time() - t0:.1f} s)")
+    host_batches, dev_batches = make_batches(torch, synth, w, args.batches, 0, dev)
+    outs = [new_logits(torch, w, w.batch, dev) for _ in range(4)]
+    log(f"{args.batches} batches of {w.batch} resident, nnz[0] = {host_batches[0].nnz} ({time.time() - t0:.1f} s)")
 
     if args.calibration_copy_mib:
         n = args.calibration_copy_mib << 20
@@ -450,174 +585,196 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    for mm in models:
-        st, pos = mm.check()
+    # ---- the timed region: exactly K steps, W warm-up steps before it
+    timed_model = pm if args.mode == "pipelined" else m
+    steps = args.steps
+    if args.graph:
+        # One replay = one in-order forward over each distinct batch.
+        per = len(dev_batches)
+        glog = [new_logits(torch, w, w.batch, dev) for _ in range(per)]
+        with torch.cuda.stream(streams[0]):
+            cap = binding.CapturedForward(m, dev_batches, glog)
+        steps = max(per, steps // per * per)
+        with torch.cuda.stream(streams[0]):
+            for _ in range(max(1, args.warmup // per)):
+                cap.replay()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        with torch.cuda.stream(streams[0]):
+            for _ in range(steps // per):
+                cap.replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t
+    else:
+        run_steps(torch, timed_model, streams[0], dev_batches, outs, args.warmup)
+        st, pos = timed_model.check()
         assert st == binding.REC_OK, (st, pos)
+        elapsed = run_steps(torch, timed_model, streams[0], dev_batches, outs, steps, first=args.warmup)
+    ms_per_step = elapsed * 1e3 / steps
+    value = w.batch * steps / elapsed
+    log(f"timed region: {steps} steps, {ms_per_step * 1e3:.1f} us/step, {value / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
 
-    # Stage events are recorded by instance 0 on every event_period-th of ITS steps.
-    use_events = not args.no_stage_events
-    steps0 = (args.steps + n_inst - 1) // n_inst            # forwards instance 0 will run
-    n_timed = (steps0 + args.event_period - 1) // args.event_period
-    if use_events:
-        m.set_profiling(n_timed, args.event_period)
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
+    extra = {}
+    # the other mode over the same K steps
+    other = m if timed_model is pm else pm
+    run_steps(torch, other, streams[0], dev_batches, outs, args.warmup)
+    dt = run_steps(torch, other, streams[0], dev_batches, outs, steps, first=args.warmup)
+    extra["in_order" if other is m else "pipelined"] = {
+        "value": w.batch * steps / dt, "unit": "samples/s", "ms_per_step": dt * 1e3 / steps, "steps": steps}
 
-    ms_per_step = elapsed * 1e3 / args.steps
-    value = w.batch * args.steps / elapsed
+    # both modes kept up for a few seconds (clocks and caches in their steady state)
+    if args.sustain_seconds > 0:
+        sus = {}
+        for label, model in (("pipelined", pm), ("in_order", m)):
+            probe = run_steps(torch, model, streams[0], dev_batches, outs, 200)
+            n = max(200, int(args.sustain_seconds / (probe / 200)) + 1)
+            dt = run_steps(torch, model, streams[0], dev_batches, outs, n)
+            sus[label] = {"value": w.batch * n / dt, "unit": "samples/s", "ms_per_step": dt * 1e3 / n,
+                          "steps": n, "seconds": dt}
+        extra["sustained"] = sus
+        log(f"sustained: pipelined {sus['pipelined']['value'] / 1e6:.2f} M, in order "
+            f"{sus['in_order']['value'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
 
-    def collect(model, count, batches_used, wl):
-        acc = np.zeros(binding.REC_NUM_STAGES)
-        for j in range(count):
-            acc += np.array(list(model.stage_ms(j).values()))
-        avg = dict(zip(binding.STAGE_NAMES, (acc / count).tolist()))
-        model.set_profiling(0)
-        pool_bytes = float(np.mean([algorithmic_pool_bytes(wl, b) for b in batches_used]))
-        achieved = pool_bytes / (avg["pool"] * 1e-3) / 1e9
-        pool = {"kernel": "pool_kernel (embedding-bag gather-reduce)", "bound": "hbm",
-                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_pool_traffic(wl, wants_streaming(wl)),
-                "bytes_per_launch": pool_bytes, "avg_launch_ms": avg["pool"],
-                "launches_timed": count,
-                "row_loads": "non-temporal" if wants_streaming(wl) else "cached"}
-        if wl.interaction != "concat":
-            return avg, pool
+    # one batch in flight at a time
+    extra["latency_ms"] = latency_profile(torch, np, m, streams[0], dev_batches, outs[0], args.latency_iters)
+    extra["latency_ms"]["note"] = "in-order forward of one batch, closed loop, host launch and synchronisation included"
+
+    # every stage of in-order forwards bracketed with HIP events
+    stage_avg, pool_ms, used = stage_profile(torch, binding, np, m, streams[0], dev_batches, args.timed_launches)
+    this_leg = pool_roofline(np, w, host_batches, used, pool_ms, wants_streaming(w))
+    comp = pool_roofline(np, w, host_batches, used, pool_ms, wants_streaming(w), kind="compulsory")
+    traffic = this_leg["traffic"]
+    pool_detail = dict(this_leg)
+    pool_detail.update({
+        "algorithmic_gbps": this_leg["achieved"],
+        "compulsory_bytes_per_launch": comp["bytes_per_launch"], "compulsory_gbps": comp["achieved"],
+        "compulsory_frac_of_hbm_peak": comp["frac"],
+        "traffic_source": "rocprofv3 counters of an earlier run of the same kernel source (profiles/), not this run",
+        "hbm_frac_by_profiled_traffic": (traffic / (this_leg["avg_launch_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS)
+        if traffic else None})
+    skewed = w.index_dist[0] == "zipf"
+    if skewed:
+        pool_detail["note"] = ("skewed ids: the caches serve most rows, so the algorithmic rate may exceed the "
+                               "HBM peak; the binding comparison is the uniform-id twin under `roofline`")
+        for k in ("frac", "achieved", "bound"):
+            pool_detail.pop(k)
+        extra["roofline_zipf"] = pool_detail
+    roofline = None if skewed and w.interaction == "dot" else this_leg
+
+    # the uniform-id twin: the run on which pooling is compared with the HBM peak
+    if skewed and w.interaction == "dot":
+        wu = w.with_uniform_indices()
+        hbu, dbu = make_batches(torch, synth, wu, args.batches, 500, dev)
+        m.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(wu)))
+        _, pool_u, used_u = stage_profile(torch, binding, np, m, streams[0], dbu, args.timed_launches)
+        st, pos = m.check()
+        assert st == binding.REC_OK, (st, pos)
+        m.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(w)))
+        roofline = pool_roofline(np, wu, hbu, used_u, pool_u, wants_streaming(wu))
+        roofline["note"] = ("uniform-id twin of the headline workload (same shapes, ids uniform): nothing for the "
+                            "caches to serve, so algorithmic bytes are HBM bytes")
+        del dbu, hbu
+    if w.interaction == "concat":
         # Dense-dominated shape: the first Predict-FC layer of all towers is one
         # launch and the longest kernel; its algorithmic work is 2 * B * K * N per tower.
-        flops = 2.0 * wl.batch * wl.top[0] * wl.top[1] * wl.towers
-        tf = flops / (avg["top_first"] * 1e-3) / 1e12
-        return avg, {"kernel": "fc_big_kernel (first Predict-FC layer of all towers, one launch)",
-                     "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                     "flops_per_launch": flops, "avg_launch_ms": avg["top_first"],
-                     "launches_timed": count, "pooling": pool}
-
-    def mlp_mfma(wl, avg):
-        """Matrix-unit use of the MLP stages: unpadded 2*M*N*K of the stage's layers over
-        its HIP-event interval (which includes one event record and, for small
-        layers, mostly launch latency) against the bf16 MFMA peak."""
-        def flops(widths):
-            return sum(2.0 * wl.batch * widths[i] * widths[i + 1] for i in range(len(widths) - 1))
-        out = {}
-        for stage, widths, mult in (("bottom", wl.bottom, 1), ("top_first", wl.top[:2], wl.towers),
-                                    ("top_rest", wl.top[1:], wl.towers)):
-            f = flops(widths) * mult
-            if f > 0 and avg[stage] > 0:
-                tf = f / (avg[stage] * 1e-3) / 1e12
-                out[stage] = {"gflop": f / 1e9, "tflops": tf, "frac_of_bf16_peak": tf / MFMA_BF16_PEAK_TFLOPS}
-        return out
-
-    stage_avg = roofline = None
-    if use_events:
-        used = [host_batches[(j * args.event_period * n_inst) % len(host_batches)] for j in range(n_timed)]
-        stage_avg, roofline = collect(m, n_timed, used, w)
-        roofline["instances_sharing_the_gpu"] = n_inst
-        extra_mlp = mlp_mfma(w, stage_avg)
-
-    # Two short extra legs, one instance alone on the GPU, every step bracketed:
-    # the same workload, and its uniform-id twin (no cache reuse: the run on
-    # which pooling is compared with the HBM peak).
-    extra = {}
-    if use_events and args.extra_steps > 0:
-        def solo(db, hb, wl):
-            for i in range(5):
-                m.forward(*db[i % len(db)], logits[0])
-            torch.cuda.synchronize()
-            m.set_profiling(args.extra_steps, 1)
-            for i in range(args.extra_steps):
-                m.forward(*db[i % len(db)], logits[0])
-            torch.cuda.synchronize()
-            return collect(m, args.extra_steps, [hb[i % len(hb)] for i in range(args.extra_steps)], wl)
-        if n_inst > 1:
-            st_solo, rf_solo = solo(dev_batches, host_batches, w)
-            extra["roofline_single_instance"] = rf_solo
-            extra["stage_ms_single_instance"] = st_solo
-        if w.index_dist[0] == "zipf" and w.interaction == "dot":
-            wu = w.with_uniform_indices()
-            hbu, dbu = make_batches(wu, 2, 500)
-            m.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(wu)))
-            st_u, rf_u = solo(dbu, hbu, wu)
-            m.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(w)))
-            extra["roofline_uniform_ids"] = rf_u
-            del dbu
+        flops = 2.0 * w.batch * w.top[0] * w.top[1] * w.towers
+        tf = flops / (stage_avg["top_first"] * 1e-3) / 1e12
+        roofline = {"kernel": "fc_big_kernel (first Predict-FC layer of all towers, one launch)",
+                    "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "flops_per_launch": flops,
+                    "avg_launch_ms": stage_avg["top_first"], "launches_timed": args.timed_launches,
+                    "pooling": this_leg}
+    log(f"stage events done ({time.time() - t0:.1f} s)")
 
     # Model co-location on the accelerator (Sec. II-B): the same K steps dealt to
-    # several instances on streams of their own; small kernels of one instance
-    # fill the gaps of the other's pooling.
-    if n_inst == 1 and args.colocated_leg > 1:
+    # several in-order instances on streams of their own.
+    if args.colocated_leg > 1:
         nc = args.colocated_leg
-        cm = [m] + [build_model(binding, synth, torch, w, w.batch, share_tables=m)[0]
-                    for _ in range(nc - 1)]
-        cs = pick_concurrent_streams(torch, dev, nc)
+        cm = [m] + [build_model(binding, synth, torch, w, w.batch, share_tables=m)[0] for _ in range(nc - 1)]
+        cs = streams if nc == 2 else pick_concurrent_streams(torch, dev, nc)
         cl = [new_logits(torch, w, w.batch, dev) for _ in range(nc)]
 
         def cstep(i):
             with torch.cuda.stream(cs[i % nc]):
                 cm[i % nc].forward(*dev_batches[i % len(dev_batches)], cl[i % nc])
+        csteps = max(steps, 200)
         for i in range(args.warmup):
             cstep(i)
         torch.cuda.synchronize()
         tc = time.perf_counter()
-        for i in range(args.steps):
+        for i in range(csteps):
             cstep(i)
         torch.cuda.synchronize()
         ec = time.perf_counter() - tc
-        extra["co_located"] = {"instances": nc, "value": w.batch * args.steps / ec,
-                               "unit": "samples/s", "ms_per_step": ec * 1e3 / args.steps,
-                               "steps": args.steps}
+        extra["co_located"] = {"instances": nc, "value": w.batch * csteps / ec, "unit": "samples/s",
+                               "ms_per_step": ec * 1e3 / csteps, "steps": csteps}
         for mm in cm[1:]:
             mm.close()
 
     # What a plain device-to-device copy reaches on this box (bytes read + written),
     # the practical yardstick beside the published peak.
-    if use_events and not args.graph:
-        n = 1 << 30
-        src = torch.empty(n, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
         dst.copy_(src)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(5):
-            dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        extra["device_copy_gbps"] = 5 * 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
-        del src, dst
+    e1.record()
+    torch.cuda.synchronize()
+    extra["device_copy_gbps"] = 5 * 2 * n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
+
+    for mm in (m, pm):
+        st, pos = mm.check()
+        assert st == binding.REC_OK, (st, pos)
+        mm.close()
+    del m, pm, dev_batches, outs
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    # ---- the other configurations, short legs
+    if not args.no_other_workloads and args.workload == "rmc2" and not args.uniform and not args.batch:
+        others = {}
+        for name in ("tiny", "rmc1", "rmc3", "mtwnd"):
+            others[name] = short_leg(torch, binding, synth, np, name, args, dev, streams)
+            gc.collect()
+            torch.cuda.empty_cache()
+        wl = synth.WORKLOADS["rmc2-large"]
+        free, _ = torch.cuda.mem_get_info()
+        need = wl.num_tables * wl.rows * wl.emb_dim * 2 + (8 << 30)
+        if free >= need:
+            others["rmc2-large"] = sweep_leg(torch, binding, synth, np, wl,
+                                             [int(x) for x in args.sweep_batches.split(",")],
+                                             args.sweep_iters, args.sla_ms, dev, streams[0])
+        else:
+            others["rmc2-large"] = {"skipped": f"needs {need >> 30} GiB of device memory, {free >> 30} GiB free"}
+        extra["other_workloads"] = others
+        gc.collect()
+        torch.cuda.empty_cache()
+        log(f"other workloads done ({time.time() - t0:.1f} s)")
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(w, host_batches, bottom, top, args.cpu_samples)
+        cpu = cpu_baseline(w, host_batches[:args.cpu_batches], bottom, top, args.cpu_samples)
 
     out = {
         "metric": ("samples/sec per GPU + embedding-bag HBM GB/s (% of peak), RMC2-style" if w.interaction == "dot"
                    else "samples/sec per GPU + first Predict-FC layer TFLOP/s (% of bf16 MFMA peak), MT-WnD-style"),
-        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 tables -> f32 accumulate; bf16 MFMA -> f32 accumulate",
-        "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.num_tables} tables x {w.rows} rows x dim {w.emb_dim} "
-                               f"{w.table_dtype}, pooling {w.pooling}, ids {w.index_dist}, "
-                               f"bottom {list(w.bottom)}, top {list(w.top)}"
-                               + (f" x {w.towers} towers, concatenation" if w.interaction == "concat" else ""),
-                   "batch": w.batch, "distinct_batches": args.batches,
-                   "co_located_instances": n_inst, "hip_graph": bool(args.graph), "hot_rows_per_table": args.hot_rows,
+        "scaling": "weak", "vs_baseline": None, "dtype": dtype_string(w), "data": "synthetic",
+        "config": {"workload": workload_string(w), "batch": w.batch, "distinct_batches": args.batches,
+                   "mode": "hip graph of in-order forwards" if args.graph else args.mode,
+                   "streams": 2 if args.mode == "pipelined" and not args.graph else 1,
+                   "hot_rows_per_table": args.hot_rows,
                    "mean_nnz": float(np.mean([b.nnz for b in host_batches]))},
-        "roofline": roofline, "cpu_baseline": cpu, "stage_ms": stage_avg,
-        "mlp_mfma": extra_mlp if use_events else None,
+        "roofline": roofline, "cpu_baseline": cpu, "stage_ms": stage_avg, "mlp_mfma": mlp_mfma(w, stage_avg),
     }
     out.update(extra)
     print(json.dumps(out), flush=True)
-    for mm in models:
-        mm.close()
     return 0
 
 

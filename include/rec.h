@@ -87,11 +87,12 @@ enum {
                               the Predict-FC input of either model shape          */
 };
 
-/* Stages timed by rec_set_profiling().  The Predict-FC is split into its first
- * layer (one launch, the widest matrix product of the model) and the rest. */
+/* Stages timed by rec_set_profiling().  Bottom-FC and Predict-FC are each split
+ * into their first launch (the widest matrix product of the stack, or the run of
+ * layers it starts) and the rest. */
 enum {
-    REC_STAGE_SCAN = 0, REC_STAGE_POOL = 1, REC_STAGE_BOTTOM = 2,
-    REC_STAGE_INTERACT = 3, REC_STAGE_TOP_FIRST = 4, REC_STAGE_TOP_REST = 5, REC_NUM_STAGES = 6
+    REC_STAGE_SCAN = 0, REC_STAGE_POOL = 1, REC_STAGE_BOTTOM_FIRST = 2, REC_STAGE_BOTTOM_REST = 3,
+    REC_STAGE_INTERACT = 4, REC_STAGE_TOP_FIRST = 5, REC_STAGE_TOP_REST = 6, REC_NUM_STAGES = 7
 };
 
 /*
@@ -260,24 +261,36 @@ enum {
      * 2: always; 0: never, every layer is a kernel of its own; 1 (default):
      * where it was measured to pay, runs that save at least one launch and
      * whose weights total at most 256 KiB (every block of such a kernel
-     * streams all weights of its run).  Same
+     * streams all weights of its run; never in a pipelined model, where its
+     * 8-wave blocks would find no room beside the pooling launch).  Same
      * arithmetic either way: bf16 operands, fp32 accumulation, the one-output
      * layer in fp32; sums are taken in a different order. */
     REC_OPT_FUSE_MLP = 2,
     /* 1: sparse-dense pipeline across batches (Sec. IV-A, "S-D pipeline": the
      * SparseNet of one query runs beside the DenseNet of another; Predict-FC
-     * waits for both, Sec. III-A).  rec_forward() then enqueues the offsets
-     * scan and the pooling on the caller's stream and Bottom-FC, interaction
-     * and Predict-FC on a second stream (rec_set_dense_stream(), else one of
-     * the library's own), ordered by events, so that the dense stages of batch
-     * i run while batch i + 1 is pooled.  The workspace holds two copies of
-     * the per-batch buffers, so the option is set before rec_workspace_bytes()
-     * and rec_bind_workspace() (REC_ERR_STATE once a workspace is bound).
-     * What changes for the caller: the logits of a call, and the caller's
-     * right to reuse that call's input buffers, are ordered on `stream` only
-     * behind the NEXT rec_forward() on it, or behind rec_drain(); all calls of
-     * one model go to one stream.  Same kernels, same results.  0 (default):
-     * everything in order on the caller's stream. */
+     * waits for both, Sec. III-A).  rec_forward() then enqueues only the
+     * pooling launch on the caller's stream, where consecutive batches'
+     * launches follow each other; the offsets scan, Bottom-FC, interaction and
+     * Predict-FC go to a second stream (rec_set_dense_stream(), else one of the
+     * library's own), ordered by events: while batch i is pooled, that stream
+     * runs interaction and Predict-FC of batch i - 1 and scan and Bottom-FC of
+     * batch i + 1.  The last two stages of a batch are enqueued by the NEXT
+     * rec_forward() or by rec_drain().  The workspace holds two copies of the
+     * per-batch buffers, so the option is set before rec_workspace_bytes() and
+     * rec_bind_workspace() (REC_ERR_STATE once a workspace is bound).
+     * What changes for the caller:
+     *   - the logits of a call, and the right to reuse or free that call's
+     *     input and output buffers, are ordered on `stream` only behind
+     *     rec_drain(); all calls of one model go to one stream;
+     *   - dev_dense and dev_lengths are read on the second stream, which is
+     *     not ordered behind `stream`: they must be complete when the call is
+     *     made, or the caller orders their producer on the stream it passed
+     *     to rec_set_dense_stream() (an event recorded on `stream` at call
+     *     time would fire only after the pooling launch before it, and the
+     *     scan would then sit between two pooling launches again).  dev_indices
+     *     is read on `stream` as usual.
+     * Same kernels, same results.  0 (default): everything in order on the
+     * caller's stream. */
     REC_OPT_PIPELINE = 3
 };
 REC_API rec_status rec_set_option(rec_model *m, int32_t option, int32_t value);
@@ -290,11 +303,12 @@ REC_API rec_status rec_set_option(rec_model *m, int32_t option, int32_t value);
  * outstanding (call rec_drain() first). */
 REC_API rec_status rec_set_dense_stream(rec_model *m, void *stream);
 
-/* Pipelined models: makes `stream` wait (on the device; the host does not
- * block) for the dense stages of every rec_forward() enqueued so far, after
- * which their logits are ordered on `stream` like any other result.  Needed
- * before ending a stream capture that contains pipelined forwards.  Does
- * nothing for a model that is not pipelined. */
+/* Pipelined models: enqueues the stages of the last rec_forward() that are
+ * still outstanding and makes `stream` wait (on the device; the host does not
+ * block) for the second stream, after which the logits of every call so far
+ * are ordered on `stream` like any other result.  Needed before ending a
+ * stream capture that contains pipelined forwards, and before rec_stage_ms()
+ * of the last call.  Does nothing for a model that is not pipelined. */
 REC_API rec_status rec_drain(rec_model *m, void *stream);
 
 /* Per-stage timing.  rec_set_profiling(m, slots, period) with slots > 0 makes
@@ -304,10 +318,11 @@ REC_API rec_status rec_drain(rec_model *m, void *stream);
  * microseconds each on the device, hence the period.  slots = 0 switches it
  * off.  rec_stage_ms() waits for the events of `slot` and fills
  * ms[REC_NUM_STAGES]; REC_ERR_STATE if that slot has not been recorded.
- * With REC_OPT_OVERLAP_DENSE the "bottom" stage is only the time the caller's
- * stream waited for Bottom-FC after pooling had finished.  With
- * REC_OPT_PIPELINE the dense stages are bracketed on their own stream (a
- * stage's time then includes whatever shared the device with it). */
+ * With REC_OPT_OVERLAP_DENSE the first Bottom-FC stage is only the time the
+ * caller's stream waited for Bottom-FC after pooling had finished, and the
+ * second reads about zero.  With REC_OPT_PIPELINE every stage but pooling is
+ * bracketed on the second stream (a stage's time then includes whatever
+ * shared the device with it). */
 REC_API rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period);
 REC_API rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms);
 

@@ -38,8 +38,8 @@ REC_OPT_OVERLAP_DENSE = 0
 REC_OPT_STREAM_ROWS = 1
 REC_OPT_FUSE_MLP = 2
 REC_OPT_PIPELINE = 3
-REC_NUM_STAGES = 6
-STAGE_NAMES = ("scan", "pool", "bottom", "interact", "top_first", "top_rest")
+REC_NUM_STAGES = 7
+STAGE_NAMES = ("scan", "pool", "bottom_first", "bottom_rest", "interact", "top_first", "top_rest")
 
 EXPORTS = ("rec_create", "rec_destroy", "rec_workspace_bytes", "rec_bind_workspace",
            "rec_load_tables", "rec_load_hot_rows", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_forward_static", "rec_check",

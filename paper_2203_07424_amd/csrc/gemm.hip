@@ -85,8 +85,13 @@ __device__ inline void load_a_chunk(AChunk<false> &c, const void *A, long long r
 // global loads in flight.  FUSE_DOT (needs BN == Npad): instead of storing C,
 // the epilogue contracts act(C) with a weight vector - the one-output last
 // layer - and writes one fp32 logit per row.
+//
+// The small tiles with two k-tiles in flight are the forms that run beside a
+// pooling launch (FcProblem::corun): they are held to 128 registers, the part of
+// a SIMD's register file that eight pooling waves leave free, so that a wave of
+// theirs needs nothing but a wave slot.
 template <int BM, int BN, int WAVES_M, int P, bool A_F32, bool OUT_F32, bool FUSE_DOT>
-__global__ __launch_bounds__(FC_THREADS) void fc_kernel(const void *__restrict__ A0, int lda,
+__global__ __launch_bounds__(FC_THREADS, (P == 2 && BM * BN <= 4096) ? 4 : 1) void fc_kernel(const void *__restrict__ A0, int lda,
                                                         long long a_stride, int M, int K, int Kpad,
                                                         const FcGroups groups, int relu,
                                                         void *__restrict__ C0, int ldc,
@@ -353,11 +358,17 @@ hipError_t launch_fc(const FcProblem &a, hipStream_t s)
     if (M <= 0) return hipSuccess;
     if (a.Kpad % BK != 0 || Npad % 64 != 0 || a.groups < 1 || a.groups > MAX_GROUPS)
         return hipErrorInvalidValue;
+    // corun: the launch shares the device with a pooling launch, whose waves
+    // (48 registers each, eight per SIMD) hold every wave slot; a wave of this
+    // kernel gets in when one of them retires, and then finds 512 - 7 * 48 = 176
+    // registers free.  With four k-tiles in flight these kernels need 184-214 and
+    // would wait for a second slot on the same SIMD, which pooling refills first
+    // (measured: 123 instead of 14 us); with three they need 130-150.
     if (a.dot_out) {
         // The block must own whole rows.
         if (Npad == 256) return launch_tile<64, 256, 1, 2>(a, s);
-        if (Npad == 128) return launch_tile<32, 128, 1, 4>(a, s);
-        if (Npad == 64) return launch_tile<64, 64, 2, 4>(a, s);
+        if (Npad == 128) return a.corun ? launch_tile<32, 128, 1, 2>(a, s) : launch_tile<32, 128, 1, 4>(a, s);
+        if (Npad == 64) return a.corun ? launch_tile<64, 64, 2, 2>(a, s) : launch_tile<64, 64, 2, 4>(a, s);
         return hipErrorInvalidValue;
     }
     if (a.num_cus > 0 && fc_big_applies(a, a.num_cus)) return launch_fc_big(a, a.num_cus, s);
@@ -365,8 +376,9 @@ hipError_t launch_fc(const FcProblem &a, hipStream_t s)
     const long long big_blocks = (long long)a.groups * (Npad / 128) * ((M + 127) / 128);
     if (Npad % 128 == 0 && big_blocks >= 256) return launch_tile<128, 128, 2, 2>(a, s);
     const long long mid_blocks = (long long)a.groups * (Npad / 64) * ((M + 63) / 64);
-    if (Npad % 128 == 0 && mid_blocks < 256) return launch_tile<32, 128, 1, 4>(a, s);
-    return launch_tile<64, 64, 2, 4>(a, s);
+    if (Npad % 128 == 0 && mid_blocks < 256)
+        return a.corun ? launch_tile<32, 128, 1, 2>(a, s) : launch_tile<32, 128, 1, 4>(a, s);
+    return a.corun ? launch_tile<64, 64, 2, 2>(a, s) : launch_tile<64, 64, 2, 4>(a, s);
 }
 
 hipError_t launch_rowdot(const void *A, bool a_f32, int lda, long long a_stride, int M, int Kpad,

@@ -83,9 +83,16 @@ struct rec_model {
     // else `side`), ordered against the caller's stream by these events.
     bool pipeline = false;
     hipStream_t dense_stream = nullptr;
-    hipEvent_t ev_in[2] = {nullptr, nullptr}, ev_pool[2] = {nullptr, nullptr}, ev_tail[2] = {nullptr, nullptr};
-    bool tail_pending[2] = {false, false};
+    hipEvent_t ev_scan[2] = {nullptr, nullptr}, ev_pool[2] = {nullptr, nullptr}, ev_tail[2] = {nullptr, nullptr};
+    bool tail_pending[2] = {false, false};  // Predict-FC of that frame's batch enqueued, not yet waited for
     int next_frame = 0, last_frame = 0;
+    // The batch whose interaction and Predict-FC are still to be enqueued (they go
+    // behind the scan and Bottom-FC of the batch after it).
+    bool have_deferred = false;
+    const float *def_dense = nullptr;
+    float *def_logits = nullptr;
+    int def_batch = 0, def_frame = 0;
+    hipEvent_t *def_ev = nullptr;
 
     // Stage timing: forward number i records into slot i % slots.
     std::vector<hipEvent_t> ev;  // slots * EV_PER_SLOT
@@ -194,8 +201,9 @@ struct Call {
 // Stage events of one timed forward (null: not timed).  Slot i of the array is
 // recorded by mark(i); which events bracket which stage depends on where the
 // stages were enqueued (stage_events()).
-enum { EV_BEGIN = 0, EV_SCAN_END = 1, EV_POOL_END = 2, EV_BOTTOM_END = 3, EV_INTERACT_END = 4,
-       EV_TOP_FIRST_END = 5, EV_END = 6, EV_BOTTOM_BEGIN = 7, EV_INTERACT_BEGIN = 8, EV_PER_SLOT = 9 };
+enum { EV_BEGIN = 0, EV_SCAN_END = 1, EV_POOL_END = 2, EV_BOTTOM_FIRST_END = 3, EV_BOTTOM_END = 4,
+       EV_INTERACT_END = 5, EV_TOP_FIRST_END = 6, EV_END = 7, EV_BOTTOM_BEGIN = 8, EV_INTERACT_BEGIN = 9,
+       EV_POOL_BEGIN = 10, EV_PER_SLOT = 11 };
 
 inline hipError_t mark(hipEvent_t *ev, int which, hipStream_t s)
 {
@@ -235,7 +243,7 @@ void chain_run(const Layer *layers, int per_stack, int G, int i, int j, ChainPro
 int chain_end(const rec_model *m, const Layer *layers, int i, int n, bool dot_after)
 {
     constexpr size_t CHAIN_AUTO_BYTES = 256 * 1024;
-    if (m->fuse_mlp == 0) return i;
+    if (m->fuse_mlp == 0 || (m->pipeline && m->fuse_mlp == 1)) return i;
     int j = i;
     size_t bytes = 0;
     while (j < n && layers[j].chain && j - i < CHAIN_MAX_LAYERS) bytes += layers[j++].chain_bytes();
@@ -245,7 +253,7 @@ int chain_end(const rec_model *m, const Layer *layers, int i, int n, bool dot_af
 }
 
 // S2: ReLU after every layer; the last one leaves fp32 for the interaction.
-hipError_t enqueue_bottom(const rec_model *m, const Bufs &u, const Call &c, hipStream_t s)
+hipError_t enqueue_bottom(const rec_model *m, const Bufs &u, const Call &c, hipStream_t s, hipEvent_t *ev)
 {
     const int n = (int)m->bottom.size();
     const Layer *layers = m->bottom.data();
@@ -269,29 +277,32 @@ hipError_t enqueue_bottom(const rec_model *m, const Bufs &u, const Call &c, hipS
             const Layer &l = layers[i];
             FcProblem p{};
             p.A = A; p.a_f32 = a_f32; p.lda = lda;
-            p.M = c.B; p.relu = true; p.groups = 1; p.num_cus = m->num_cus;
+            p.M = c.B; p.relu = true; p.groups = 1; p.num_cus = m->num_cus; p.corun = m->pipeline;
             p.K = l.K; p.Kpad = l.Kpad; p.Npad = l.Npad;
             p.g.W[0] = l.W; p.g.bias[0] = l.bias;
             p.C = C; p.out_f32 = last; p.ldc = ldc;
             REC_TRY(launch_fc(p, s));
         }
         A = C; lda = ldc; a_f32 = false;
-        ++launches;
+        if (launches++ == 0) REC_TRY(mark(ev, EV_BOTTOM_FIRST_END, s));  // the first launch is timed on its own
         i = upto;
     }
-    return hipSuccess;
+    if (launches == 0) REC_TRY(mark(ev, EV_BOTTOM_FIRST_END, s));
+    return mark(ev, EV_BOTTOM_END, s);
 }
 
 // S0 and S1.  With hot lists registered (and use_hot), hot rows are served from
 // LDS.  In the concatenation model the sums go straight into the Predict-FC
 // input rows.
-hipError_t enqueue_sparse(const rec_model *m, const Bufs &u, const Call &c, bool use_hot, hipStream_t s,
-                          hipEvent_t *ev)
+hipError_t enqueue_scan(const rec_model *m, const Bufs &u, const Call &c, hipStream_t s)
+{
+    return launch_scan(c.lengths, m->T * c.B, c.nnz, u.offsets, u.tile_sums, u.err, s);
+}
+
+hipError_t enqueue_pool(const rec_model *m, const Bufs &u, const Call &c, bool use_hot, hipStream_t s)
 {
     const int B = c.B, T = m->T, D = m->D;
     const bool concat = m->interaction == REC_INTERACT_CONCAT;
-    REC_TRY(launch_scan(c.lengths, T * B, c.nnz, u.offsets, u.tile_sums, u.err, s));
-    REC_TRY(mark(ev, EV_SCAN_END, s));
     int hmax = 0;
     if (use_hot)
         for (const TableDesc &d : m->desc) hmax = d.n_hot > hmax ? d.n_hot : hmax;
@@ -310,6 +321,15 @@ hipError_t enqueue_sparse(const rec_model *m, const Bufs &u, const Call &c, bool
         REC_TRY(launch_pool(u.tables, m->dtype, T, D, B, c.indices, u.offsets, out, c.nnz, m->stream_rows,
                             m->max_rows, u.err, s));
     }
+    return hipSuccess;
+}
+
+hipError_t enqueue_sparse(const rec_model *m, const Bufs &u, const Call &c, bool use_hot, hipStream_t s,
+                          hipEvent_t *ev)
+{
+    REC_TRY(enqueue_scan(m, u, c, s));
+    REC_TRY(mark(ev, EV_SCAN_END, s));
+    REC_TRY(enqueue_pool(m, u, c, use_hot, s));
     return mark(ev, EV_POOL_END, s);
 }
 
@@ -335,7 +355,7 @@ hipError_t enqueue_tail(const rec_model *m, const Bufs &u, const Call &c, hipStr
     const int G = m->towers, n_top = m->n_top;
     FcProblem p{};
     p.A = u.act[0]; p.a_f32 = false; p.lda = m->z_ld; p.a_stride = 0;
-    p.M = B; p.relu = true; p.groups = G; p.num_cus = m->num_cus;
+    p.M = B; p.relu = true; p.groups = G; p.num_cus = m->num_cus; p.corun = m->pipeline;
     for (int k = 0; k < G; ++k) {
         const Layer &dotl = m->top[(size_t)k * n_top + n_top - 1];
         p.g.dot_w[k] = static_cast<const float *>(dotl.W);
@@ -402,8 +422,7 @@ hipError_t enqueue_in_order(const rec_model *m, const Bufs &u, const Call &c, bo
 {
     REC_TRY(mark(ev, EV_BEGIN, s));
     REC_TRY(enqueue_sparse(m, u, c, use_hot, s, ev));
-    REC_TRY(enqueue_bottom(m, u, c, s));
-    REC_TRY(mark(ev, EV_BOTTOM_END, s));
+    REC_TRY(enqueue_bottom(m, u, c, s, ev));
     return enqueue_tail(m, u, c, s, ev);
 }
 
@@ -468,6 +487,23 @@ __global__ __launch_bounds__(64) void static_end_kernel(const ErrRecord *err, lo
     }
     fault[0] = st;
     fault[1] = pos;
+}
+
+// Pipelined model: interaction and Predict-FC of the batch that was pooled last,
+// on the second stream behind that pooling launch.
+hipError_t enqueue_deferred(rec_model *m, hipStream_t d)
+{
+    if (!m->have_deferred) return hipSuccess;
+    const int k = m->def_frame;
+    const Bufs u = bufs_at(m->ws, m->lay, k);
+    const Call c{m->def_dense, nullptr, nullptr, m->def_batch, 0, m->def_logits};
+    REC_TRY(hipStreamWaitEvent(d, m->ev_pool[k], 0));
+    REC_TRY(mark(m->def_ev, EV_INTERACT_BEGIN, d));
+    REC_TRY(enqueue_tail(m, u, c, d, m->def_ev));
+    REC_TRY(hipEventRecord(m->ev_tail[k], d));
+    m->tail_pending[k] = true;
+    m->have_deferred = false;
+    return hipSuccess;
 }
 
 // Host-checkable faults of a forward call.
@@ -592,7 +628,7 @@ void rec_destroy(rec_model *m)
     if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
     if (m->ev_join) (void)hipEventDestroy(m->ev_join);
     for (int k = 0; k < 2; ++k)
-        for (hipEvent_t e : {m->ev_in[k], m->ev_pool[k], m->ev_tail[k]})
+        for (hipEvent_t e : {m->ev_scan[k], m->ev_pool[k], m->ev_tail[k]})
             if (e) (void)hipEventDestroy(e);
     if (m->side) (void)hipStreamDestroy(m->side);
     delete m;
@@ -611,13 +647,14 @@ rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *s
             hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess)
             return REC_ERR_DEVICE;
         for (int k = 0; k < 2; ++k)
-            if (hipEventCreateWithFlags(&m->ev_in[k], hipEventDisableTiming) != hipSuccess ||
+            if (hipEventCreateWithFlags(&m->ev_scan[k], hipEventDisableTiming) != hipSuccess ||
                 hipEventCreateWithFlags(&m->ev_pool[k], hipEventDisableTiming) != hipSuccess ||
                 hipEventCreateWithFlags(&m->ev_tail[k], hipEventDisableTiming) != hipSuccess)
                 return REC_ERR_DEVICE;
     }
     m->tail_pending[0] = m->tail_pending[1] = false;
     m->next_frame = m->last_frame = 0;
+    m->have_deferred = false;
     if (fc_big_prepare() != hipSuccess || chain_prepare() != hipSuccess) return REC_ERR_DEVICE;
     {   // set-up is also where the static scratch of this device is looked up
         char *unused = nullptr;
@@ -719,36 +756,34 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
     } while (0)
 
     if (m->pipeline) {
-        // Sparse stage (S0, S1) on the caller's stream, dense stages (S2; S3, S4)
-        // on the second stream: the dense stages of this batch run beside the
-        // sparse stage of the next one (Sec. IV-A, S-D pipeline).  Frame k holds
+        // Pooling (S1) on the caller's stream, everything else on the second
+        // stream: while batch i is pooled, that stream runs the interaction and
+        // Predict-FC of batch i - 1 and the scan and Bottom-FC of batch i + 1
+        // (Sec. IV-A, S-D pipeline; dependencies of Sec. III-A).  Frame k holds
         // what this batch passes through; the batch before it used the other one.
+        // Order on the second stream: scan(i), Bottom-FC(i), then the deferred
+        // interaction and Predict-FC of batch i - 1, so that the next pooling launch
+        // never waits behind a stage that itself waits for the current one.
         const int k = m->next_frame;
         const Bufs u = bufs_at(m->ws, m->lay, k);
         hipStream_t d = m->dense_stream ? m->dense_stream : m->side;
-        // The inputs are ready at this point of the caller's stream.
-        REC_DEV(hipEventRecord(m->ev_in[k], s));
-        REC_DEV(hipStreamWaitEvent(d, m->ev_in[k], 0));
+        REC_DEV(mark(ev, EV_BEGIN, d));
+        REC_DEV(enqueue_scan(m, u, c, d));
+        REC_DEV(mark(ev, EV_SCAN_END, d));
+        REC_DEV(hipEventRecord(m->ev_scan[k], d));
         if (!m->bottom.empty()) {
             REC_DEV(mark(ev, EV_BOTTOM_BEGIN, d));
-            REC_DEV(enqueue_bottom(m, u, c, d));
-            REC_DEV(mark(ev, EV_BOTTOM_END, d));
+            REC_DEV(enqueue_bottom(m, u, c, d, ev));
         }
-        REC_DEV(mark(ev, EV_BEGIN, s));
-        REC_DEV(enqueue_sparse(m, u, c, true, s, ev));
+        REC_DEV(hipStreamWaitEvent(s, m->ev_scan[k], 0));
+        REC_DEV(mark(ev, EV_POOL_BEGIN, s));
+        REC_DEV(enqueue_pool(m, u, c, true, s));
+        REC_DEV(mark(ev, EV_POOL_END, s));
         REC_DEV(hipEventRecord(m->ev_pool[k], s));
-        // The dense stages of the batch before this one have had a whole
-        // pooling launch to finish: behind it the caller's stream waits for
-        // them, which makes their logits visible to it and frees their frame.
-        if (m->tail_pending[k ^ 1]) {
-            REC_DEV(hipStreamWaitEvent(s, m->ev_tail[k ^ 1], 0));
-            m->tail_pending[k ^ 1] = false;
-        }
-        REC_DEV(hipStreamWaitEvent(d, m->ev_pool[k], 0));
-        REC_DEV(mark(ev, EV_INTERACT_BEGIN, d));
-        REC_DEV(enqueue_tail(m, u, c, d, ev));
-        REC_DEV(hipEventRecord(m->ev_tail[k], d));
-        m->tail_pending[k] = true;
+        if (enqueue_deferred(m, d) != hipSuccess) return REC_ERR_DEVICE;
+        m->have_deferred = true;
+        m->def_dense = dev_dense; m->def_logits = dev_logits; m->def_batch = batch; m->def_frame = k;
+        m->def_ev = ev;
         m->last_frame = k;
         m->next_frame = k ^ 1;
         if (prof) m->slot_mode[slot] = 1;
@@ -761,11 +796,12 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
             REC_DEV(mark(ev, EV_BEGIN, s));
             REC_DEV(hipEventRecord(m->ev_fork, s));
             REC_DEV(hipStreamWaitEvent(m->side, m->ev_fork, 0));
-            REC_DEV(enqueue_bottom(m, u, c, m->side));
+            REC_DEV(enqueue_bottom(m, u, c, m->side, nullptr));
             REC_DEV(hipEventRecord(m->ev_join, m->side));
             REC_DEV(enqueue_sparse(m, u, c, true, s, ev));
             // the "bottom" stage then times only what pooling did not hide
             REC_DEV(hipStreamWaitEvent(s, m->ev_join, 0));
+            REC_DEV(mark(ev, EV_BOTTOM_FIRST_END, s));
             REC_DEV(mark(ev, EV_BOTTOM_END, s));
             REC_DEV(enqueue_tail(m, u, c, s, ev));
         } else {
@@ -819,6 +855,9 @@ rec_status rec_drain(rec_model *m, void *stream)
 {
     if (!m) return REC_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (m->have_deferred &&
+        enqueue_deferred(m, m->dense_stream ? m->dense_stream : m->side) != hipSuccess)
+        return REC_ERR_DEVICE;
     for (int k = 0; k < 2; ++k)
         if (m->tail_pending[k]) {
             if (hipStreamWaitEvent(s, m->ev_tail[k], 0) != hipSuccess) return REC_ERR_DEVICE;
@@ -894,7 +933,7 @@ rec_status rec_set_dense_stream(rec_model *m, void *stream)
 {
     if (!m) return REC_ERR_ARG;
     for (int k = 0; k < 2; ++k)
-        if (m->tail_pending[k]) return REC_ERR_STATE;  // work is still ordered on the old one
+        if (m->tail_pending[k] || m->have_deferred) return REC_ERR_STATE;  // work is still ordered on the old one
     m->dense_stream = static_cast<hipStream_t>(stream);
     return REC_OK;
 }
@@ -904,6 +943,7 @@ rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period)
     if (!m || slots < 0 || slots > 65536 || (slots > 0 && period < 1)) return REC_ERR_ARG;
     for (hipEvent_t e : m->ev)
         if (e) (void)hipEventDestroy(e);
+    m->def_ev = nullptr;  // a deferred Predict-FC is then enqueued untimed
     m->ev.assign((size_t)slots * EV_PER_SLOT, nullptr);
     m->slot_mode.assign((size_t)slots, 0);
     m->slots = 0;
@@ -921,19 +961,23 @@ rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms)
     const long long timed = (m->forwards + m->period - 1) / m->period;  // timed forwards so far
     if (m->slots <= 0 || slot < 0 || slot >= m->slots || slot >= timed) return REC_ERR_STATE;
     hipEvent_t *ev = &m->ev[(size_t)slot * EV_PER_SLOT];
+    // A pipelined forward's last stages are enqueued by the next call or by rec_drain().
+    if (m->have_deferred && m->def_ev == ev) return REC_ERR_STATE;
     // Stage i ran between events begin[i] and end[i]; in a pipelined forward the
     // dense stages sit on another stream and have begin events of their own.
-    static const int end[REC_NUM_STAGES] = {EV_SCAN_END, EV_POOL_END, EV_BOTTOM_END, EV_INTERACT_END,
-                                            EV_TOP_FIRST_END, EV_END};
-    static const int begin_in_order[REC_NUM_STAGES] = {EV_BEGIN, EV_SCAN_END, EV_POOL_END, EV_BOTTOM_END,
-                                                       EV_INTERACT_END, EV_TOP_FIRST_END};
-    static const int begin_pipelined[REC_NUM_STAGES] = {EV_BEGIN, EV_SCAN_END, EV_BOTTOM_BEGIN,
-                                                        EV_INTERACT_BEGIN, EV_INTERACT_END, EV_TOP_FIRST_END};
+    static const int end[REC_NUM_STAGES] = {EV_SCAN_END, EV_POOL_END, EV_BOTTOM_FIRST_END, EV_BOTTOM_END,
+                                            EV_INTERACT_END, EV_TOP_FIRST_END, EV_END};
+    static const int begin_in_order[REC_NUM_STAGES] = {EV_BEGIN, EV_SCAN_END, EV_POOL_END, EV_BOTTOM_FIRST_END,
+                                                       EV_BOTTOM_END, EV_INTERACT_END, EV_TOP_FIRST_END};
+    static const int begin_pipelined[REC_NUM_STAGES] = {EV_BEGIN, EV_POOL_BEGIN, EV_BOTTOM_BEGIN,
+                                                        EV_BOTTOM_FIRST_END, EV_INTERACT_BEGIN,
+                                                        EV_INTERACT_END, EV_TOP_FIRST_END};
     const int *begin = m->slot_mode[slot] ? begin_pipelined : begin_in_order;
     if (hipEventSynchronize(ev[EV_END]) != hipSuccess) return REC_ERR_DEVICE;
     for (int i = 0; i < REC_NUM_STAGES; ++i) {
         ms[i] = 0.0f;
-        if (m->slot_mode[slot] && i == REC_STAGE_BOTTOM && m->bottom.empty()) continue;
+        if (m->slot_mode[slot] && (i == REC_STAGE_BOTTOM_FIRST || i == REC_STAGE_BOTTOM_REST) && m->bottom.empty())
+            continue;
         if (hipEventElapsedTime(&ms[i], ev[begin[i]], ev[end[i]]) != hipSuccess) return REC_ERR_DEVICE;
     }
     return REC_OK;

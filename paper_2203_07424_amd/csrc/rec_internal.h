@@ -91,6 +91,7 @@ struct FcProblem {
     FcGroups g;
     float *dot_out; int dot_ld;
     int num_cus;  // compute units of the device; 0 = unknown (never picks the wide-tile kernels)
+    bool corun;   // the launch will share the device with a pooling launch: keep register use low
 };
 bool fc_can_fuse_dot(int Npad);
 hipError_t launch_fc(const FcProblem &p, hipStream_t s);

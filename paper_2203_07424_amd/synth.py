@@ -205,14 +205,17 @@ def draw_lengths(w: Workload, batch_id: int) -> np.ndarray:
 
 
 def draw_indices(w: Workload, batch_id: int, lengths: np.ndarray,
-                 cdf: Optional[np.ndarray] = None) -> np.ndarray:
-    """Row ids, int32 [sum(lengths)], concatenated in the order of `lengths`."""
+                 cdf: Optional[np.ndarray] = None, workers: int = 1) -> np.ndarray:
+    """Row ids, int32 [sum(lengths)], concatenated in the order of `lengths`.
+    Every table has a stream of its own, so `workers` threads may draw the
+    tables side by side; the result does not depend on their number."""
     per_table = lengths.reshape(w.num_tables, w.batch).sum(axis=1, dtype=np.int64)
     out = np.empty(int(per_table.sum()), dtype=np.int32)
     if w.index_dist[0] == "zipf" and cdf is None:
         cdf = zipf_cdf(w.rows, float(w.index_dist[1]))
-    pos = 0
-    for t in range(w.num_tables):
+    starts = np.concatenate([[0], np.cumsum(per_table)])
+
+    def one_table(t: int) -> None:
         n = int(per_table[t])
         g = _rng(w.seed, "indices", batch_id, t)
         if w.index_dist[0] == "uniform":
@@ -222,8 +225,15 @@ def draw_indices(w: Workload, batch_id: int, lengths: np.ndarray,
             rank = np.minimum(np.searchsorted(cdf, u, side="right"), w.rows - 1)
             a, c = rank_permutation(w.seed, t, w.rows)
             ids = (rank.astype(np.int64) * a + c) % w.rows
-        out[pos:pos + n] = ids
-        pos += n
+        out[int(starts[t]):int(starts[t]) + n] = ids
+
+    if workers > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(one_table, range(w.num_tables)))
+    else:
+        for t in range(w.num_tables):
+            one_table(t)
     return out
 
 
@@ -283,9 +293,9 @@ class Batch:
         self.nnz = int(self.indices.shape[0])
 
 
-def draw_batch(w: Workload, batch_id: int, cdf: Optional[np.ndarray] = None) -> Batch:
+def draw_batch(w: Workload, batch_id: int, cdf: Optional[np.ndarray] = None, workers: int = 1) -> Batch:
     lengths = draw_lengths(w, batch_id)
-    return Batch(draw_dense(w, batch_id), draw_indices(w, batch_id, lengths, cdf), lengths)
+    return Batch(draw_dense(w, batch_id), draw_indices(w, batch_id, lengths, cdf, workers), lengths)
 
 
 # --------------------------------------------------------------------------

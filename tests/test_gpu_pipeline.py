@@ -1,6 +1,6 @@
-"""The sparse-dense pipeline (REC_OPT_PIPELINE): scan and pooling of batch i + 1
-on the caller's stream beside Bottom-FC, interaction and Predict-FC of batch i
-on a second stream.  Same kernels as the in-order pass, so the logits must be
+"""The sparse-dense pipeline (REC_OPT_PIPELINE): pooling launches back to back
+on the caller's stream, scan, Bottom-FC, interaction and Predict-FC of the
+neighbouring batches beside them on a second stream.  Same kernels as the in-order pass, so the logits must be
 bit-equal to it, and they are held to the oracle's bars as well.
 """
 import numpy as np
@@ -42,6 +42,11 @@ def test_pipelined_forwards_equal_in_order_forwards(binding, name, own_dense_str
     main = torch.cuda.Stream()
     side = torch.cuda.Stream() if own_dense_stream else None
     pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side)
+    # Left to itself a pipelined model runs every layer as a kernel of its own (the
+    # chain kernel's 8-wave blocks find no room beside pooling), which sums in a
+    # different order than a chain: compare like with like.
+    ref.set_option(binding.REC_OPT_FUSE_MLP, 0)
+    pm.set_option(binding.REC_OPT_FUSE_MLP, 0)
     tabs = [synth.full_table(w, t) for t in range(w.num_tables)]
     batches = [synth.draw_batch(w.with_batch(B), 60 + i) for i, B in enumerate(sizes)]
     data = [dev(b) for b in batches]
@@ -73,34 +78,61 @@ def test_pipelined_forwards_equal_in_order_forwards(binding, name, own_dense_str
     ref.close()
 
 
-def test_pipelined_results_are_ordered_behind_the_next_call(binding):
-    """Without a drain the logits of call i are ordered on the caller's stream
-    behind call i + 1: a copy enqueued there sees them complete."""
+def test_pipelined_results_are_ordered_behind_drain(binding):
+    """Work enqueued on the caller's stream behind rec_drain() sees the logits of
+    every call so far, also when drains and forwards alternate, with the
+    library's own second stream and with one the caller brings."""
     w = synth.WORKLOADS["tiny"]
-    say("pipeline: ordering behind the next call")
+    say("pipeline: ordering behind drain")
     ref, _, _ = H.make_workload_model(binding, w)
-    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True,
-                                     dense_stream=torch.cuda.Stream())
+    ref.set_option(binding.REC_OPT_FUSE_MLP, 0)
     batches = [synth.draw_batch(w, 80 + i) for i in range(6)]
     data = [dev(b) for b in batches]
     want = [ref.forward(*d).cpu().numpy() for d in data]
-    main = torch.cuda.Stream()
-    outs = [torch.empty(w.batch, dtype=torch.float32, device="cuda") for _ in data]
-    snaps = []
-    with torch.cuda.stream(main):
-        for i, (d, o) in enumerate(zip(data, outs)):
-            pm.forward(*d, o)
-            if i > 0:
-                snaps.append(outs[i - 1].clone())       # enqueued on `main`, behind call i
-    main.synchronize()
-    for i, sn in enumerate(snaps):
-        assert np.array_equal(sn.cpu().numpy(), want[i]), i
-    assert pm.check() == (binding.REC_OK, -1)            # check() drains
-    assert np.array_equal(outs[-1].cpu().numpy(), want[-1])
-    # the option decides the workspace size: not changeable once one is bound
-    assert binding.rec_set_option(pm.handle, binding.REC_OPT_PIPELINE, 0) == binding.REC_ERR_STATE
-    pm.close()
+    torch.cuda.synchronize()
+    for mode, side in ((1, torch.cuda.Stream()), (2, None)):
+        pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side)
+        main = torch.cuda.Stream()
+        outs = [torch.empty(w.batch, dtype=torch.float32, device="cuda") for _ in data]
+        snaps = {}
+        with torch.cuda.stream(main):
+            for i, (d, o) in enumerate(zip(data, outs)):
+                pm.forward(*d, o)
+                if i in (0, 3):                        # a drain in the middle of the run
+                    pm.drain()
+                    snaps[i] = [outs[j].clone() for j in range(i + 1)]
+            pm.drain()
+            final = [o.clone() for o in outs]
+        main.synchronize()
+        for i, sn in snaps.items():
+            for j, t in enumerate(sn):
+                assert np.array_equal(t.cpu().numpy(), want[j]), (mode, i, j)
+        for j, t in enumerate(final):
+            assert np.array_equal(t.cpu().numpy(), want[j]), (mode, j)
+        assert pm.check() == (binding.REC_OK, -1)
+        # the option decides the workspace size: not changeable once one is bound
+        assert binding.rec_set_option(pm.handle, binding.REC_OPT_PIPELINE, 0) == binding.REC_ERR_STATE
+        pm.close()
     ref.close()
+
+
+def test_pipelined_stage_timing(binding):
+    """Stage events of a pipelined forward: readable after rec_drain(), every stage positive."""
+    w = synth.WORKLOADS["tiny"]
+    say("pipeline: stage events")
+    pm, _, _ = H.make_workload_model(binding, w, pipeline=True)
+    d = dev(synth.draw_batch(w, 5))
+    pm.set_profiling(3, 1)
+    for _ in range(3):
+        pm.forward(*d)
+    assert binding.rec_stage_ms(pm.handle, 2)[0] == binding.REC_ERR_STATE     # its last stages are not enqueued yet
+    pm.drain()
+    torch.cuda.synchronize()
+    for slot in range(3):
+        ms = pm.stage_ms(slot)
+        assert all(v > 0 for v in ms.values()), ms
+    pm.set_profiling(0)
+    pm.close()
 
 
 def test_pipelined_faults_are_reported(binding):
@@ -125,6 +157,7 @@ def test_full_size_pipelined_whole_batches_against_oracle(binding):
     w = synth.WORKLOADS["rmc2"]
     say("full-size pipelined", w.name)
     ref, bottom, top = H.make_workload_model(binding, w)
+    ref.set_option(binding.REC_OPT_FUSE_MLP, 0)
     main, side = torch.cuda.Stream(), torch.cuda.Stream()
     pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side)
     batches = [synth.draw_batch(w, 20 + i) for i in range(4)]
