@@ -289,8 +289,9 @@ enum {
      *     time would fire only after the pooling launch before it, and the
      *     scan would then sit between two pooling launches again).  dev_indices
      *     is read on `stream` as usual.
-     * Same kernels, same results.  0 (default): everything in order on the
-     * caller's stream. */
+     * Same kernels, same results.  Under stream capture the second stream
+     * forks from `stream` at every call and rejoins it in rec_drain().
+     * 0 (default): everything in order on the caller's stream. */
     REC_OPT_PIPELINE = 3
 };
 REC_API rec_status rec_set_option(rec_model *m, int32_t option, int32_t value);

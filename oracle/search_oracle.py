@@ -27,35 +27,41 @@ Point = Tuple[int, int]                       # (index into m_values, index into
 Measure = Callable[[int, int], Tuple[float, float, float]]
 
 
+def _moves(p: Point, n_m: int, n_d: int) -> List[Point]:
+    """Grid points one step away in the directions the search may take: a larger
+    batch, one more co-located instance, or both."""
+    mi, di = p
+    steps = [(mi, di + 1), (mi + 1, di), (mi + 1, di + 1)]
+    return [q for q in steps if q[0] < n_m and q[1] < n_d]
+
+
 def algorithm1(measure: Measure, n_m: int, n_d: int, L: float,
                P: float = float("inf")) -> Tuple[Optional[Point], List[Point]]:
-    """Returns (configuration or None if even the origin breaks the bounds, path)."""
-    cur = (0, 0)                                            # Initialize batch size, num of threads
-    qps_prev, lat_prev, pow_prev = measure(*cur)
-    if not (lat_prev < L and pow_prev < P):
-        return None, [cur]
-    path = [cur]
+    """Hill climb over the (instances, batch) grid from its smallest corner
+    (Algorithm 1, Sec. IV-A, restricted to P_sp(M+D)).  Returns (end point, or
+    None when even the starting corner is out of bounds; points visited)."""
+    def admissible(lat: float, power: float) -> bool:
+        return lat < L and power < P
+
+    here: Point = (0, 0)
+    here_qps, lat0, pow0 = measure(*here)
+    visited = [here]
+    if not admissible(lat0, pow0):
+        return None, visited
     while True:
-        mi, di = cur
-        candidates = [(mi, di + 1), (mi + 1, di), (mi + 1, di + 1)]   # three candidates
-        grad_qps, valid = [], []
-        for c in candidates:
-            if c[0] >= n_m or c[1] >= n_d:
-                grad_qps.append(float("-inf"))
-                valid.append(False)
-                continue
-            qps_t, lat_t, pow_t = measure(*c)
-            grad_qps.append(qps_t - qps_prev)               # nabla QPS = QPS_t - QPS_{t-1}
-            valid.append(lat_t < L and pow_t < P)           # nabla Latency decides through L
-        best, best_gain = None, 0.0
-        for c, g, ok in zip(candidates, grad_qps, valid):
-            if ok and g > best_gain:
-                best, best_gain = c, g
-        if best is None:                                    # no throughput increase within bounds
-            return cur, path
-        cur = best                                          # update to Configuration(max(Candidate))
-        qps_prev = qps_prev + best_gain
-        path.append(cur)
+        # throughput gained by each admissible move, measured against the point we stand on
+        gains = {}
+        for q in _moves(here, n_m, n_d):
+            qps, lat, power = measure(*q)
+            if admissible(lat, power):
+                gains[q] = qps - here_qps
+        # the first of the best: ties keep the order batch, instances, both
+        winner = max(gains, key=gains.get, default=None)
+        if winner is None or gains[winner] <= 0.0:
+            return here, visited
+        here_qps += gains[winner]
+        here = winner
+        visited.append(here)
 
 
 def exhaustive(measure: Measure, n_m: int, n_d: int, L: float,

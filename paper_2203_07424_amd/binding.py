@@ -386,11 +386,13 @@ class CapturedForward:
         assert len(self.batches) == len(self.logits) and self.batches
         for (d, i, l), out in zip(self.batches, self.logits):   # warm-up outside capture
             model.forward(d, i, l, out)
+        model.drain()
         torch.cuda.synchronize(model.device)
         self.graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(self.graph):
             for (d, i, l), out in zip(self.batches, self.logits):
                 model.forward(d, i, l, out)
+            model.drain()       # a pipelined model's second stream joins the capture here
 
     def replay(self) -> None:
         self.graph.replay()

@@ -84,6 +84,7 @@ struct rec_model {
     bool pipeline = false;
     hipStream_t dense_stream = nullptr;
     hipEvent_t ev_scan[2] = {nullptr, nullptr}, ev_pool[2] = {nullptr, nullptr}, ev_tail[2] = {nullptr, nullptr};
+    hipEvent_t ev_fork2 = nullptr;  // under stream capture: pulls the second stream into the capture
     bool tail_pending[2] = {false, false};  // Predict-FC of that frame's batch enqueued, not yet waited for
     int next_frame = 0, last_frame = 0;
     // The batch whose interaction and Predict-FC are still to be enqueued (they go
@@ -630,6 +631,7 @@ void rec_destroy(rec_model *m)
     for (int k = 0; k < 2; ++k)
         for (hipEvent_t e : {m->ev_scan[k], m->ev_pool[k], m->ev_tail[k]})
             if (e) (void)hipEventDestroy(e);
+    if (m->ev_fork2) (void)hipEventDestroy(m->ev_fork2);
     if (m->side) (void)hipStreamDestroy(m->side);
     delete m;
 }
@@ -644,7 +646,8 @@ rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *s
         // Default priority; the two events only order work, they carry no timing.
         if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess)
+            hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&m->ev_fork2, hipEventDisableTiming) != hipSuccess)
             return REC_ERR_DEVICE;
         for (int k = 0; k < 2; ++k)
             if (hipEventCreateWithFlags(&m->ev_scan[k], hipEventDisableTiming) != hipSuccess ||
@@ -767,6 +770,15 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         const int k = m->next_frame;
         const Bufs u = bufs_at(m->ws, m->lay, k);
         hipStream_t d = m->dense_stream ? m->dense_stream : m->side;
+        // While the caller's stream is being captured into a graph, the second
+        // stream has to fork from it before its first launch, or that launch would
+        // run at once instead of being recorded.
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        REC_DEV(hipStreamIsCapturing(s, &capturing));
+        if (capturing == hipStreamCaptureStatusActive) {
+            REC_DEV(hipEventRecord(m->ev_fork2, s));
+            REC_DEV(hipStreamWaitEvent(d, m->ev_fork2, 0));
+        }
         REC_DEV(mark(ev, EV_BEGIN, d));
         REC_DEV(enqueue_scan(m, u, c, d));
         REC_DEV(mark(ev, EV_SCAN_END, d));

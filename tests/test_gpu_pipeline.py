@@ -135,6 +135,34 @@ def test_pipelined_stage_timing(binding):
     pm.close()
 
 
+def test_pipelined_forwards_in_a_graph(binding):
+    """Three pipelined forwards and the drain recorded into one HIP graph (the second
+    stream forks from and joins the captured one through the library's events);
+    every replay, with eager work in between, gives the in-order bits."""
+    w = synth.WORKLOADS["tiny"]
+    say("pipeline: graph replay")
+    ref, _, _ = H.make_workload_model(binding, w)
+    ref.set_option(binding.REC_OPT_FUSE_MLP, 0)
+    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True)
+    batches = [synth.draw_batch(w, 90 + i) for i in range(3)]
+    data = [dev(b) for b in batches]
+    want = [ref.forward(*d).cpu().numpy() for d in data]
+    outs = [torch.empty(w.batch, dtype=torch.float32, device="cuda") for _ in data]
+    torch.cuda.synchronize()
+    cap = binding.CapturedForward(pm, data, outs)
+    for rep in range(3):
+        for o in outs:
+            o.zero_()
+        cap.replay()
+        torch.cuda.synchronize()
+        for j, o in enumerate(outs):
+            assert np.array_equal(o.cpu().numpy(), want[j]), (rep, j)
+        assert np.array_equal(ref.forward(*data[rep]).cpu().numpy(), want[rep])   # eager work between replays
+    assert pm.check() == (binding.REC_OK, -1)
+    pm.close()
+    ref.close()
+
+
 def test_pipelined_faults_are_reported(binding):
     w = synth.WORKLOADS["tiny"].with_batch(64)
     say("pipeline: device faults")
