@@ -314,6 +314,44 @@ def mlp_mfma(wl, avg):
     return out
 
 
+def library_gemm_yardstick(torch, M, N, K, dev, reps=30):
+    """What the vendor's GEMM library (through torch.matmul) reaches on bf16
+    operands of one layer's shape on this machine: a yardstick beside the published
+    peak, like the device copy is for HBM.  Not part of the forward pass."""
+    a = torch.randn(M, K, device=dev, dtype=torch.bfloat16)
+    b = torch.randn(N, K, device=dev, dtype=torch.bfloat16)
+    for _ in range(5):
+        c = a @ b.t()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        c = a @ b.t()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+    del a, b, c
+    return {"shape_m_n_k": [M, N, K], "ms": ms, "tflops": tf, "frac_of_bf16_peak": tf / MFMA_BF16_PEAK_TFLOPS,
+            "what": "torch.matmul (vendor GEMM library) on bf16 operands of the same shape, back to back, by events; "
+                    "no bias, no activation"}
+
+
+def widest_layer_yardstick(torch, wl, dev):
+    """The library yardstick for the widest matrix product of the workload (first
+    Bottom-FC layer, or first Predict-FC layer of all towers side by side)."""
+    cands = []
+    if len(wl.bottom) > 1:
+        cands.append(("bottom_first", wl.batch, wl.bottom[1], wl.bottom[0]))
+    cands.append(("top_first", wl.batch, wl.top[1] * wl.towers, wl.top[0]))
+    stage, M, N, K = max(cands, key=lambda c: c[1] * c[2] * c[3])
+    if 2.0 * M * N * K < 1e10:      # small layers are launch-bound either way
+        return None
+    y = library_gemm_yardstick(torch, M, N, K, dev)
+    y["stage"] = stage
+    return y
+
+
 def pool_roofline(np, wl, hb, used, pool_ms, streaming, kind="algorithmic"):
     """The pooling kernel against the HBM peak: bytes per launch over the mean
     launch time of the timed launches."""
@@ -358,6 +396,9 @@ def short_leg(torch, binding, synth, np, name, args, dev, streams):
     avg, pool_ms, used = stage_profile(torch, binding, np, m, streams[0], db, 32)
     res["stage_ms"] = avg
     res["mlp_mfma"] = mlp_mfma(w, avg)
+    y = widest_layer_yardstick(torch, w, dev)
+    if y:
+        res["library_gemm_yardstick"] = y
     res["pooling"] = pool_roofline(np, w, hb, used, pool_ms, streaming)
     if w.index_dist[0] == "zipf":      # cache-served: an algorithmic rate, not a fraction of the HBM peak
         res["pooling"]["algorithmic_gbps"] = res["pooling"].pop("achieved")
@@ -513,8 +554,8 @@ def main() -> int:
                     help="register the N most frequent rows of each table (profiled on two "
                          "batches that are not timed) so that pooling serves them from LDS")
     ap.add_argument("--graph", action="store_true",
-                    help="record the distinct batches' in-order forwards into one HIP graph and replay "
-                         "it (steps are rounded to whole replays)")
+                    help="record the distinct batches' forwards (in the chosen --mode) into one HIP graph "
+                         "and replay it (steps are rounded to whole replays)")
     ap.add_argument("--stream-rows", choices=["auto", "on", "off"], default="auto",
                     help="pooling loads table rows with the non-temporal hint; auto = only for "
                          "workloads whose ids are drawn uniformly (no reuse for the caches to serve)")
@@ -585,15 +626,31 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # Both modes kept up for a few seconds each, before the timed region, so that
+    # the K timed steps below see the clocks and caches of a device that has been
+    # serving for a while rather than one that idled through the input set-up.
+    extra = {}
+    if args.sustain_seconds > 0:
+        sus = {}
+        for label, model in (("pipelined", pm), ("in_order", m)):
+            probe = run_steps(torch, model, streams[0], dev_batches, outs, 200)
+            n = max(200, int(args.sustain_seconds / (probe / 200)) + 1)
+            dt = run_steps(torch, model, streams[0], dev_batches, outs, n)
+            sus[label] = {"value": w.batch * n / dt, "unit": "samples/s", "ms_per_step": dt * 1e3 / n,
+                          "steps": n, "seconds": dt}
+        extra["sustained"] = sus
+        log(f"sustained: pipelined {sus['pipelined']['value'] / 1e6:.2f} M, in order "
+            f"{sus['in_order']['value'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
+
     # ---- the timed region: exactly K steps, W warm-up steps before it
     timed_model = pm if args.mode == "pipelined" else m
     steps = args.steps
     if args.graph:
-        # One replay = one in-order forward over each distinct batch.
+        # One replay = one forward over each distinct batch (in the chosen mode).
         per = len(dev_batches)
         glog = [new_logits(torch, w, w.batch, dev) for _ in range(per)]
         with torch.cuda.stream(streams[0]):
-            cap = binding.CapturedForward(m, dev_batches, glog)
+            cap = binding.CapturedForward(timed_model, dev_batches, glog)
         steps = max(per, steps // per * per)
         with torch.cuda.stream(streams[0]):
             for _ in range(max(1, args.warmup // per)):
@@ -614,26 +671,12 @@ def main() -> int:
     value = w.batch * steps / elapsed
     log(f"timed region: {steps} steps, {ms_per_step * 1e3:.1f} us/step, {value / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
 
-    extra = {}
     # the other mode over the same K steps
     other = m if timed_model is pm else pm
     run_steps(torch, other, streams[0], dev_batches, outs, args.warmup)
     dt = run_steps(torch, other, streams[0], dev_batches, outs, steps, first=args.warmup)
     extra["in_order" if other is m else "pipelined"] = {
         "value": w.batch * steps / dt, "unit": "samples/s", "ms_per_step": dt * 1e3 / steps, "steps": steps}
-
-    # both modes kept up for a few seconds (clocks and caches in their steady state)
-    if args.sustain_seconds > 0:
-        sus = {}
-        for label, model in (("pipelined", pm), ("in_order", m)):
-            probe = run_steps(torch, model, streams[0], dev_batches, outs, 200)
-            n = max(200, int(args.sustain_seconds / (probe / 200)) + 1)
-            dt = run_steps(torch, model, streams[0], dev_batches, outs, n)
-            sus[label] = {"value": w.batch * n / dt, "unit": "samples/s", "ms_per_step": dt * 1e3 / n,
-                          "steps": n, "seconds": dt}
-        extra["sustained"] = sus
-        log(f"sustained: pipelined {sus['pipelined']['value'] / 1e6:.2f} M, in order "
-            f"{sus['in_order']['value'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
 
     # one batch in flight at a time
     extra["latency_ms"] = latency_profile(torch, np, m, streams[0], dev_batches, outs[0], args.latency_iters)
@@ -684,6 +727,9 @@ def main() -> int:
                     "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "flops_per_launch": flops,
                     "avg_launch_ms": stage_avg["top_first"], "launches_timed": args.timed_launches,
                     "pooling": this_leg}
+    y = widest_layer_yardstick(torch, w, dev)
+    if y:
+        extra["library_gemm_yardstick"] = y
     log(f"stage events done ({time.time() - t0:.1f} s)")
 
     # Model co-location on the accelerator (Sec. II-B): the same K steps dealt to
@@ -767,7 +813,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dtype_string(w), "data": "synthetic",
         "config": {"workload": workload_string(w), "batch": w.batch, "distinct_batches": args.batches,
-                   "mode": "hip graph of in-order forwards" if args.graph else args.mode,
+                   "mode": f"hip graph of {args.mode} forwards" if args.graph else args.mode,
                    "streams": 2 if args.mode == "pipelined" and not args.graph else 1,
                    "hot_rows_per_table": args.hot_rows,
                    "mean_nnz": float(np.mean([b.nnz for b in host_batches]))},
