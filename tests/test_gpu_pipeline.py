@@ -163,6 +163,45 @@ def test_pipelined_forwards_in_a_graph(binding):
     ref.close()
 
 
+def test_pipelined_edge_calls(binding):
+    """Empty batches, hot-row lists and option changes in a pipelined model."""
+    w = synth.WORKLOADS["tiny"].with_batch(96)
+    say("pipeline: edge calls")
+    ref, _, _ = H.make_workload_model(binding, w)
+    ref.set_option(binding.REC_OPT_FUSE_MLP, 0)
+    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True)
+    b = synth.draw_batch(w, 11)
+    d, i, l = dev(b)
+    want = ref.forward(d, i, l).cpu().numpy()
+    out = torch.empty(w.batch, dtype=torch.float32, device="cuda")
+    pm.forward(d, i, l, out)
+    # a batch of zero samples enqueues nothing and leaves the outstanding call alone
+    assert binding.rec_forward(pm.handle, d, i, l, 0, 0, out) == binding.REC_OK
+    # the second stream cannot be swapped while work is outstanding on it
+    assert binding.rec_set_dense_stream(pm.handle, None) == binding.REC_ERR_STATE
+    pm.drain()
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+    side = torch.cuda.Stream()
+    assert binding.rec_set_dense_stream(pm.handle, side) == binding.REC_OK
+    pm.dense_stream = side
+    # hot-row lists: the LDS-cached pooling kernel inside the pipeline, same sums
+    hot = synth.profile_hot_rows(w, [3, 4], 64)
+    for t in range(w.num_tables):
+        pm.load_hot_rows(t, hot[t])
+    out2 = torch.empty_like(out)
+    pm.forward(d, i, l, out2)
+    pm.drain()
+    torch.cuda.synchronize()
+    exact = orc.forward(b.dense, [synth.full_table(w, t) for t in range(w.num_tables)], b.indices, b.lengths,
+                        synth.draw_mlp(w, "bottom"), synth.draw_mlp(w, "top"))
+    H.check_logits(out2.cpu().numpy(), exact["logits"])
+    assert np.abs(out2.cpu().numpy() - want).max() <= 1e-4 * np.abs(want).max()
+    assert pm.check() == (binding.REC_OK, -1)
+    pm.close()
+    ref.close()
+
+
 def test_pipelined_faults_are_reported(binding):
     w = synth.WORKLOADS["tiny"].with_batch(64)
     say("pipeline: device faults")

@@ -98,6 +98,17 @@ def test_static_scratch_reports_faults_and_rejects_what_does_not_fit(binding):
     torch.cuda.synchronize()
     assert fault.tolist() == [binding.REC_OK, -1]
     assert torch.isfinite(out).all()
+    # a batch of zero samples runs no stage and still reports a clean record
+    fault.fill_(7)
+    assert static(m.handle, d.data_ptr(), i.data_ptr(), l.data_ptr(), 0, 0, out.data_ptr(),
+                  fault.data_ptr(), stream) == binding.REC_OK
+    torch.cuda.synchronize()
+    assert fault.tolist() == [binding.REC_OK, -1]
+    # host-checkable faults are refused as in rec_forward
+    assert static(m.handle, d.data_ptr(), i.data_ptr(), l.data_ptr(), 65, batch.nnz, out.data_ptr(),
+                  None, stream) == binding.REC_ERR_ARG
+    assert static(m.handle, None, i.data_ptr(), l.data_ptr(), 64, batch.nnz, out.data_ptr(),
+                  None, stream) == binding.REC_ERR_ARG
     m.close()
     # a batch whose intermediates exceed the static array is refused, nothing is enqueued
     big = synth.WORKLOADS["tiny"].with_batch(1 << 17)
