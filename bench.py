@@ -6,9 +6,9 @@ bag pooling, Bottom-FC, pairwise-dot interaction, Predict-FC.  Inputs and
 tables are resident in HBM before the timed region.  Prints ONE JSON line.
 
 Default run (workload rmc2, the configuration the metric is quoted on):
-  value               K steps through the pipelined model (pooling launches back to
-                      back on one stream, the dense stages of the neighbouring
-                      batches beside them on a second one), drained and synchronised
+  value               K steps through the pipelined model (four streams: scan and
+                      Bottom-FC, two pooling streams taken in turn, interaction and
+                      Predict-FC; four batches in flight), drained and synchronised
   in_order            the same K steps with everything in order on one stream
   sustained           the pipelined loop kept up for at least two seconds
   latency_ms          one batch at a time, host launch and synchronisation included
@@ -157,7 +157,8 @@ def cpu_baseline(w, batches, bottom, top, n_samples: int) -> dict:
 FUSE_MLP = "auto"   # --fuse-mlp: how runs of narrow FC layers are launched
 
 
-def build_model(binding, synth, torch, w, max_batch, share_tables=None, pipeline=False, dense_stream=None):
+def build_model(binding, synth, torch, w, max_batch, share_tables=None, pipeline=False, dense_stream=None,
+                pool_streams=(None, None)):
     """Model of workload `w` with tables filled on the device (or shared with
     the model `share_tables`) and packed MLPs."""
     dev = torch.device("cuda:0")
@@ -166,7 +167,7 @@ def build_model(binding, synth, torch, w, max_batch, share_tables=None, pipeline
                          w.num_dense, list(w.bottom), list(w.top), max_batch,
                          min(max_batch * w.num_tables * hi, 2 ** 31 - 1),
                          interaction=w.interaction, towers=w.towers, pipeline=pipeline,
-                         dense_stream=dense_stream)
+                         dense_stream=dense_stream, pool_streams=pool_streams)
     tdt = torch.float16 if w.table_dtype == "f16" else torch.float32
     for t in range(w.num_tables):
         if share_tables is not None:
@@ -296,6 +297,9 @@ def latency_profile(torch, np, model, stream, db, out, iters, warmup=10):
             "iterations": iters}
 
 
+SUSTAINED_RANDOM_TFLOPS = None   # set by main() once mfma_sustained() has run
+
+
 def mlp_mfma(wl, avg):
     """Matrix-unit use of the FC stages: unpadded 2*M*N*K of the stage's layers over
     its HIP-event interval (which includes one event record and, for small
@@ -311,6 +315,8 @@ def mlp_mfma(wl, avg):
             tf = f / (avg[stage] * 1e-3) / 1e12
             out[stage] = {"gflop": f / 1e9, "ms": avg[stage], "tflops": tf,
                           "frac_of_bf16_peak": tf / MFMA_BF16_PEAK_TFLOPS}
+            if SUSTAINED_RANDOM_TFLOPS:
+                out[stage]["frac_of_sustained_rate_on_random_operands"] = tf / SUSTAINED_RANDOM_TFLOPS
     return out
 
 
@@ -335,6 +341,37 @@ def library_gemm_yardstick(torch, M, N, K, dev, reps=30):
     return {"shape_m_n_k": [M, N, K], "ms": ms, "tflops": tf, "frac_of_bf16_peak": tf / MFMA_BF16_PEAK_TFLOPS,
             "what": "torch.matmul (vendor GEMM library) on bf16 operands of the same shape, back to back, by events; "
                     "no bias, no activation"}
+
+
+def mfma_sustained(torch, binding, dev):
+    """The bf16 matrix rate this device sustains on nothing but matrix
+    instructions (rec_probe_mfma: register operands, 8 wavefronts per compute
+    unit): on constant operands, on random ones, and on random ones with a quarter
+    of the compute units busy.  With the whole chip busy the rate is power-limited
+    and depends on the operand bits, so the middle figure, not the published peak,
+    is what a GEMM on real data can reach here."""
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    out = {"compute_units": cus}
+    iters = 2000
+    for label, rnd, blocks in (("constant_operands", False, cus), ("random_operands", True, cus),
+                               ("random_operands_quarter_of_the_chip", True, max(1, cus // 4))):
+        assert binding.rec_probe_mfma(rnd, blocks, 200, sink) == binding.REC_OK     # warm-up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        assert binding.rec_probe_mfma(rnd, blocks, iters, sink) == binding.REC_OK
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        flops = float(blocks) * 8 * iters * 32 * 32768
+        tf = flops / (ms * 1e-3) / 1e12
+        out[label] = {"blocks": blocks, "ms": ms, "tflops": tf,
+                      "tflops_per_compute_unit": tf / blocks,
+                      "frac_of_bf16_peak": tf / (MFMA_BF16_PEAK_TFLOPS * blocks / cus)}
+    out["what"] = ("rec_probe_mfma: v_mfma_f32_32x32x16_bf16 on register operands only, one workgroup of 8 wavefronts "
+                   "per compute unit; fractions are of the published peak scaled to the compute units in use")
+    return out
 
 
 def widest_layer_yardstick(torch, wl, dev):
@@ -377,7 +414,7 @@ def short_leg(torch, binding, synth, np, name, args, dev, streams):
     t0 = time.time()
     m, _, _ = build_model(binding, synth, torch, w, w.batch)
     pm, _, _ = build_model(binding, synth, torch, w, w.batch, share_tables=m, pipeline=True,
-                           dense_stream=streams[1])
+                           dense_stream=streams[3], pool_streams=(streams[1], streams[2]))
     streaming = w.index_dist[0] == "uniform"
     for mm in (m, pm):
         mm.set_option(binding.REC_OPT_STREAM_ROWS, int(streaming))
@@ -534,7 +571,7 @@ def main() -> int:
     ap.add_argument("--uniform", action="store_true", help="uniform ids instead of Zipf")
     ap.add_argument("--batches", type=int, default=8, help="distinct input batches cycled")
     ap.add_argument("--mode", choices=["pipelined", "in-order"], default="pipelined",
-                    help="what the timed region runs: the sparse-dense pipeline over two streams, "
+                    help="what the timed region runs: the sparse-dense pipeline over four streams, "
                          "or everything in order on one stream")
     ap.add_argument("--colocated-leg", type=int, default=2,
                     help="instances of the co-located leg (0 or 1 = none)")
@@ -596,14 +633,17 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     t0 = time.time()
-    streams = pick_concurrent_streams(torch, dev, 2)
+    global SUSTAINED_RANDOM_TFLOPS
+    SUSTAINED = mfma_sustained(torch, binding, dev)
+    SUSTAINED_RANDOM_TFLOPS = SUSTAINED["random_operands"]["tflops"]
+    streams = pick_concurrent_streams(torch, dev, 4)
 
     def wants_streaming(wl):
         return args.stream_rows == "on" or (args.stream_rows == "auto" and wl.index_dist[0] == "uniform")
 
     m, bottom, top = build_model(binding, synth, torch, w, w.batch)
     pm, _, _ = build_model(binding, synth, torch, w, w.batch, share_tables=m, pipeline=True,
-                           dense_stream=streams[1])
+                           dense_stream=streams[3], pool_streams=(streams[1], streams[2]))
     for mm in (m, pm):
         mm.set_option(binding.REC_OPT_STREAM_ROWS, int(wants_streaming(w)))
     if args.hot_rows > 0:
@@ -730,6 +770,7 @@ def main() -> int:
     y = widest_layer_yardstick(torch, w, dev)
     if y:
         extra["library_gemm_yardstick"] = y
+    extra["mfma_sustained"] = SUSTAINED
     log(f"stage events done ({time.time() - t0:.1f} s)")
 
     # Model co-location on the accelerator (Sec. II-B): the same K steps dealt to
@@ -737,7 +778,7 @@ def main() -> int:
     if args.colocated_leg > 1:
         nc = args.colocated_leg
         cm = [m] + [build_model(binding, synth, torch, w, w.batch, share_tables=m)[0] for _ in range(nc - 1)]
-        cs = streams if nc == 2 else pick_concurrent_streams(torch, dev, nc)
+        cs = streams[:nc] if nc <= len(streams) else pick_concurrent_streams(torch, dev, nc)
         cl = [new_logits(torch, w, w.batch, dev) for _ in range(nc)]
 
         def cstep(i):
@@ -814,7 +855,7 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": dtype_string(w), "data": "synthetic",
         "config": {"workload": workload_string(w), "batch": w.batch, "distinct_batches": args.batches,
                    "mode": f"hip graph of {args.mode} forwards" if args.graph else args.mode,
-                   "streams": 2 if args.mode == "pipelined" and not args.graph else 1,
+                   "streams": 4 if args.mode == "pipelined" else 1,
                    "hot_rows_per_table": args.hot_rows,
                    "mean_nnz": float(np.mean([b.nnz for b in host_batches]))},
         "roofline": roofline, "cpu_baseline": cpu, "stage_ms": stage_avg, "mlp_mfma": mlp_mfma(w, stage_avg),

@@ -267,49 +267,49 @@ enum {
      * layer in fp32; sums are taken in a different order. */
     REC_OPT_FUSE_MLP = 2,
     /* 1: sparse-dense pipeline across batches (Sec. IV-A, "S-D pipeline": the
-     * SparseNet of one query runs beside the DenseNet of another; Predict-FC
-     * waits for both, Sec. III-A).  rec_forward() then enqueues only the
-     * pooling launch on the caller's stream, where consecutive batches'
-     * launches follow each other; the offsets scan, Bottom-FC, interaction and
-     * Predict-FC go to a second stream (rec_set_dense_stream(), else one of the
-     * library's own), ordered by events: while batch i is pooled, that stream
-     * runs interaction and Predict-FC of batch i - 1 and scan and Bottom-FC of
-     * batch i + 1.  The last two stages of a batch are enqueued by the NEXT
-     * rec_forward() or by rec_drain().  The workspace holds two copies of the
-     * per-batch buffers, so the option is set before rec_workspace_bytes() and
-     * rec_bind_workspace() (REC_ERR_STATE once a workspace is bound).
-     * What changes for the caller:
-     *   - the logits of a call, and the right to reuse or free that call's
-     *     input and output buffers, are ordered on `stream` only behind
-     *     rec_drain(); all calls of one model go to one stream;
-     *   - dev_dense and dev_lengths are read on the second stream, which is
-     *     not ordered behind `stream`: they must be complete when the call is
-     *     made, or the caller orders their producer on the stream it passed
-     *     to rec_set_dense_stream() (an event recorded on `stream` at call
-     *     time would fire only after the pooling launch before it, and the
-     *     scan would then sit between two pooling launches again).  dev_indices
-     *     is read on `stream` as usual.
-     * Same kernels, same results.  Under stream capture the second stream
-     * forks from `stream` at every call and rejoins it in rec_drain().
+     * SparseNet of one query runs beside the DenseNet of others; Predict-FC
+     * waits for both, Sec. III-A).  rec_forward() then spreads a batch over four
+     * streams, ordered by events: the offsets scan and Bottom-FC on the
+     * caller's stream, the pooling launch on one of two pooling streams taken in
+     * turn (rec_set_pool_streams()), interaction and Predict-FC on the dense
+     * stream (rec_set_dense_stream()).  The caller's stream never waits for
+     * pooling, so while two pooling launches are in flight the other streams
+     * run the first stages of later batches and the last stages of earlier ones.
+     * The workspace holds four copies of the per-batch buffers (a batch owns one
+     * until its logits are written; the fifth call makes the caller's stream
+     * wait for the first), so the option is set before rec_workspace_bytes()
+     * and rec_bind_workspace() (REC_ERR_STATE once a workspace is bound).
+     * What changes for the caller: every input is still read in stream order
+     * behind `stream`, but the logits of a call, and the right to reuse or free
+     * that call's input and output buffers, are ordered on `stream` only behind
+     * rec_drain(); all calls of one model go to one stream.
+     * Same kernels, same results.  Under stream capture the other streams fork
+     * from `stream` through those events and rejoin it in rec_drain().
      * 0 (default): everything in order on the caller's stream. */
     REC_OPT_PIPELINE = 3
 };
 REC_API rec_status rec_set_option(rec_model *m, int32_t option, int32_t value);
 
-/* The stream on which a pipelined model (REC_OPT_PIPELINE) runs its dense
- * stages: a hipStream_t of default priority that the caller owns and keeps
- * alive, ideally one that the device runs beside `stream` of rec_forward()
- * (streams share a few hardware queues; two on the same queue take turns).
- * NULL: a stream of the library's own.  REC_ERR_STATE while dense stages are
+/* The stream on which a pipelined model (REC_OPT_PIPELINE) runs interaction
+ * and Predict-FC: a hipStream_t of default priority that the caller owns and
+ * keeps alive, ideally one that the device runs beside the others (streams
+ * share a few hardware queues; two on the same queue take turns).
+ * NULL: a stream of the library's own.  REC_ERR_STATE while stages are
  * outstanding (call rec_drain() first). */
 REC_API rec_status rec_set_dense_stream(rec_model *m, void *stream);
 
-/* Pipelined models: enqueues the stages of the last rec_forward() that are
- * still outstanding and makes `stream` wait (on the device; the host does not
- * block) for the second stream, after which the logits of every call so far
- * are ordered on `stream` like any other result.  Needed before ending a
- * stream capture that contains pipelined forwards, and before rec_stage_ms()
- * of the last call.  Does nothing for a model that is not pipelined. */
+/* The two streams on which a pipelined model runs its pooling launches in
+ * turn: hipStream_t of default priority that the caller owns and keeps alive,
+ * ideally on hardware queues of their own beside `stream` of rec_forward() and
+ * the dense stream.  NULL for either: a stream of the library's own.
+ * REC_ERR_STATE while stages are outstanding (call rec_drain() first). */
+REC_API rec_status rec_set_pool_streams(rec_model *m, void *stream_a, void *stream_b);
+
+/* Pipelined models: makes `stream` wait (on the device; the host does not
+ * block) for the outstanding stages of every call so far, after which their
+ * logits are ordered on `stream` like any other result.  Needed before ending
+ * a stream capture that contains pipelined forwards.  Does nothing for a model
+ * that is not pipelined. */
 REC_API rec_status rec_drain(rec_model *m, void *stream);
 
 /* Per-stage timing.  rec_set_profiling(m, slots, period) with slots > 0 makes
@@ -321,9 +321,9 @@ REC_API rec_status rec_drain(rec_model *m, void *stream);
  * ms[REC_NUM_STAGES]; REC_ERR_STATE if that slot has not been recorded.
  * With REC_OPT_OVERLAP_DENSE the first Bottom-FC stage is only the time the
  * caller's stream waited for Bottom-FC after pooling had finished, and the
- * second reads about zero.  With REC_OPT_PIPELINE every stage but pooling is
- * bracketed on the second stream (a stage's time then includes whatever
- * shared the device with it). */
+ * second reads about zero.  With REC_OPT_PIPELINE every stage is bracketed on
+ * the stream it runs on (a stage's time then includes whatever shared the
+ * device with it). */
 REC_API rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period);
 REC_API rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms);
 

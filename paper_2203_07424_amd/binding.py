@@ -43,8 +43,8 @@ STAGE_NAMES = ("scan", "pool", "bottom_first", "bottom_rest", "interact", "top_f
 
 EXPORTS = ("rec_create", "rec_destroy", "rec_workspace_bytes", "rec_bind_workspace",
            "rec_load_tables", "rec_load_hot_rows", "rec_mlp_packed_bytes", "rec_load_mlp", "rec_forward", "rec_forward_static", "rec_check",
-           "rec_debug_get", "rec_set_option", "rec_set_dense_stream", "rec_drain", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
-           "rec_synth_fill_table")
+           "rec_debug_get", "rec_set_option", "rec_set_dense_stream", "rec_set_pool_streams", "rec_drain", "rec_set_profiling", "rec_stage_ms", "rec_status_string",
+           "rec_synth_fill_table", "rec_probe_mfma")
 
 
 class rec_config(C.Structure):
@@ -85,6 +85,8 @@ _lib.rec_set_option.restype = C.c_int
 _lib.rec_set_option.argtypes = [_vp, C.c_int32, C.c_int32]
 _lib.rec_set_dense_stream.restype = C.c_int
 _lib.rec_set_dense_stream.argtypes = [_vp, _vp]
+_lib.rec_set_pool_streams.restype = C.c_int
+_lib.rec_set_pool_streams.argtypes = [_vp, _vp, _vp]
 _lib.rec_drain.restype = C.c_int
 _lib.rec_drain.argtypes = [_vp, _vp]
 _lib.rec_set_profiling.restype = C.c_int
@@ -95,6 +97,10 @@ _lib.rec_status_string.restype = C.c_char_p
 _lib.rec_status_string.argtypes = [C.c_int]
 _lib.rec_synth_fill_table.restype = C.c_int
 _lib.rec_synth_fill_table.argtypes = [_vp, C.c_int32, C.c_uint64, C.c_int32, C.c_int64, C.c_int32, _vp]
+
+
+_lib.rec_probe_mfma.restype = C.c_int
+_lib.rec_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
 
 
 class RecError(RuntimeError):
@@ -196,6 +202,10 @@ def rec_set_dense_stream(m: int, stream: Optional["torch.cuda.Stream"]) -> int:
     return _lib.rec_set_dense_stream(m, None if stream is None else stream.cuda_stream)
 
 
+def rec_set_pool_streams(m: int, a: Optional["torch.cuda.Stream"], b: Optional["torch.cuda.Stream"]) -> int:
+    return _lib.rec_set_pool_streams(m, None if a is None else a.cuda_stream, None if b is None else b.cuda_stream)
+
+
 def rec_drain(m: int) -> int:
     return _lib.rec_drain(m, _stream())
 
@@ -216,6 +226,11 @@ def rec_synth_fill_table(dev_rows: torch.Tensor, seed: int, table: int) -> int:
                                      dev_rows.shape[1], _stream())
 
 
+def rec_probe_mfma(random_operands: bool, blocks: int, iters: int, dev_sink: Optional[torch.Tensor]) -> int:
+    """One launch of nothing but bf16 matrix instructions (blocks * 8 * iters * 32 * 32768 flops)."""
+    return _lib.rec_probe_mfma(int(bool(random_operands)), int(blocks), int(iters), _ptr(dev_sink), _stream())
+
+
 class RecModel:
     """Owns the device buffers of one model and forwards batches through the library."""
 
@@ -223,7 +238,8 @@ class RecModel:
                  num_dense: int, bottom_widths: Sequence[int], top_widths: Sequence[int],
                  max_batch: int, max_nnz: int, device: str = "cuda:0", interaction: str = "dot",
                  towers: int = 1, pipeline: bool = False,
-                 dense_stream: Optional["torch.cuda.Stream"] = None):
+                 dense_stream: Optional["torch.cuda.Stream"] = None,
+                 pool_streams: Sequence[Optional["torch.cuda.Stream"]] = (None, None)):
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the forward pass has no CPU path")
         self.device = torch.device(device)
@@ -239,10 +255,11 @@ class RecModel:
                                      inter, towers)
         if st != REC_OK:
             raise RecError(st, "rec_create")
-        self.pipeline, self.dense_stream = bool(pipeline), dense_stream
+        self.pipeline, self.dense_stream, self.pool_streams = bool(pipeline), dense_stream, tuple(pool_streams)
         if pipeline:      # decides the workspace size, so it is set before binding
             self._ok(rec_set_option(self.handle, REC_OPT_PIPELINE, 1), "rec_set_option")
             self._ok(rec_set_dense_stream(self.handle, dense_stream), "rec_set_dense_stream")
+            self._ok(rec_set_pool_streams(self.handle, *self.pool_streams), "rec_set_pool_streams")
         self.ws = torch.empty(rec_workspace_bytes(self.handle), dtype=torch.uint8, device=self.device)
         self._ok(rec_bind_workspace(self.handle, self.ws), "rec_bind_workspace")
         self.tables: List[Optional[torch.Tensor]] = [None] * num_tables
@@ -392,7 +409,7 @@ class CapturedForward:
         with torch.cuda.graph(self.graph):
             for (d, i, l), out in zip(self.batches, self.logits):
                 model.forward(d, i, l, out)
-            model.drain()       # a pipelined model's second stream joins the capture here
+            model.drain()       # a pipelined model's other streams join the capture here
 
     def replay(self) -> None:
         self.graph.replay()

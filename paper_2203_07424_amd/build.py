@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "librec_mi355x.so")
 
-SOURCES = ["scan.hip", "pool.hip", "pool_hot.hip", "gemm.hip", "gemm_big.hip", "mlp_chain.hip", "interact.hip", "synth_fill.hip", "rec_api.hip"]
+SOURCES = ["scan.hip", "pool.hip", "pool_hot.hip", "gemm.hip", "gemm_big.hip", "mlp_chain.hip", "interact.hip", "synth_fill.hip", "probe.hip", "rec_api.hip"]
 
 # The packed-fp32 target feature is switched off for all device code.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -37,7 +37,8 @@ def _compile(src: str, force: bool, sanitize: bool = False) -> str:
     s = os.path.join(CSRC, src)
     o = os.path.join(OBJ_SAN if sanitize else OBJ, src + ".o")
     deps = [s, os.path.join(CSRC, "rec_internal.h"), os.path.join(ROOT, "include", "rec.h"),
-            os.path.join(ROOT, "include", "rec_synth.h"), os.path.abspath(__file__)]
+            os.path.join(ROOT, "include", "rec_synth.h"), os.path.join(ROOT, "include", "rec_probe.h"),
+            os.path.abspath(__file__)]
     if not force and os.path.exists(o) and all(os.path.getmtime(o) >= os.path.getmtime(d) for d in deps):
         return o
     r = subprocess.run([_hipcc(), *FLAGS, *(SAN_FLAGS if sanitize else []), "-c", s, "-o", o],

@@ -40,13 +40,14 @@ struct Layer {
 // Where the parts of a forward's scratch memory sit inside one block of device
 // memory (byte offsets; every part 256-byte aligned).  The error record and the
 // table descriptors exist once; what one batch passes through (a frame) once
-// or twice.
+// up to four times.
+constexpr int MAX_FRAMES = 4;
 struct Frame {
     size_t off_offsets = 0, off_tile_sums = 0, off_pooled = 0, off_x0 = 0, off_act[3] = {0, 0, 0};
 };
 struct Carve {
     size_t off_err = 0, off_tables = 0, bytes = 0;
-    Frame fr[2];
+    Frame fr[MAX_FRAMES];
 };
 
 struct rec_model {
@@ -78,22 +79,18 @@ struct rec_model {
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
-    // Sparse-dense pipeline: batches alternate between two frames of the
-    // workspace; the dense stages run on a second stream (the caller's choice,
-    // else `side`), ordered against the caller's stream by these events.
+    // Sparse-dense pipeline: a batch owns one of four frames of the workspace
+    // until its logits are written.  Scan and Bottom-FC run on the caller's
+    // stream, pooling on two streams in turn, interaction and Predict-FC on a
+    // fourth; these events order them.
     bool pipeline = false;
-    hipStream_t dense_stream = nullptr;
-    hipEvent_t ev_scan[2] = {nullptr, nullptr}, ev_pool[2] = {nullptr, nullptr}, ev_tail[2] = {nullptr, nullptr};
-    hipEvent_t ev_fork2 = nullptr;  // under stream capture: pulls the second stream into the capture
-    bool tail_pending[2] = {false, false};  // Predict-FC of that frame's batch enqueued, not yet waited for
+    hipStream_t dense_stream = nullptr;              // the caller's choice, else `side`
+    hipStream_t pool_stream[2] = {nullptr, nullptr}; // the caller's choice, else own_stream
+    hipStream_t own_stream[2] = {nullptr, nullptr};
+    hipEvent_t ev_scan[MAX_FRAMES] = {}, ev_bottom[MAX_FRAMES] = {}, ev_pool[MAX_FRAMES] = {}, ev_tail[MAX_FRAMES] = {};
+    bool tail_pending[MAX_FRAMES] = {};  // Predict-FC of that frame's batch enqueued, not yet waited for
     int next_frame = 0, last_frame = 0;
-    // The batch whose interaction and Predict-FC are still to be enqueued (they go
-    // behind the scan and Bottom-FC of the batch after it).
-    bool have_deferred = false;
-    const float *def_dense = nullptr;
-    float *def_logits = nullptr;
-    int def_batch = 0, def_frame = 0;
-    hipEvent_t *def_ev = nullptr;
+    int pool_turn = 0;                   // which pooling stream takes the next batch
 
     // Stage timing: forward number i records into slot i % slots.
     std::vector<hipEvent_t> ev;  // slots * EV_PER_SLOT
@@ -108,7 +105,7 @@ struct rec_model {
 namespace {
 
 // Scratch layout of model m for batches of up to `batch` samples, with `frames`
-// (1 or 2) copies of the per-batch part.
+// (1 or MAX_FRAMES) copies of the per-batch part.
 Carve carve(const rec_model *m, int batch, int frames)
 {
     const bool concat = m->interaction == REC_INTERACT_CONCAT;
@@ -129,7 +126,7 @@ Carve carve(const rec_model *m, int batch, int frames)
         fr.off_act[1] = o; o += align_up((size_t)batch * m->act_row_bytes);
         fr.off_act[2] = o; o += align_up((size_t)batch * m->act_row_bytes);
     }
-    if (frames < 2) c.fr[1] = c.fr[0];
+    for (int f = frames; f < MAX_FRAMES; ++f) c.fr[f] = c.fr[0];
     c.bytes = o;
     return c;
 }
@@ -490,23 +487,6 @@ __global__ __launch_bounds__(64) void static_end_kernel(const ErrRecord *err, lo
     fault[1] = pos;
 }
 
-// Pipelined model: interaction and Predict-FC of the batch that was pooled last,
-// on the second stream behind that pooling launch.
-hipError_t enqueue_deferred(rec_model *m, hipStream_t d)
-{
-    if (!m->have_deferred) return hipSuccess;
-    const int k = m->def_frame;
-    const Bufs u = bufs_at(m->ws, m->lay, k);
-    const Call c{m->def_dense, nullptr, nullptr, m->def_batch, 0, m->def_logits};
-    REC_TRY(hipStreamWaitEvent(d, m->ev_pool[k], 0));
-    REC_TRY(mark(m->def_ev, EV_INTERACT_BEGIN, d));
-    REC_TRY(enqueue_tail(m, u, c, d, m->def_ev));
-    REC_TRY(hipEventRecord(m->ev_tail[k], d));
-    m->tail_pending[k] = true;
-    m->have_deferred = false;
-    return hipSuccess;
-}
-
 // Host-checkable faults of a forward call.
 rec_status check_call(const rec_model *m, const float *dev_dense, const int32_t *dev_indices,
                       const int32_t *dev_lengths, int32_t batch, int64_t nnz, const float *dev_logits)
@@ -628,10 +608,11 @@ void rec_destroy(rec_model *m)
         if (e) (void)hipEventDestroy(e);
     if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
     if (m->ev_join) (void)hipEventDestroy(m->ev_join);
-    for (int k = 0; k < 2; ++k)
-        for (hipEvent_t e : {m->ev_scan[k], m->ev_pool[k], m->ev_tail[k]})
+    for (int k = 0; k < MAX_FRAMES; ++k)
+        for (hipEvent_t e : {m->ev_scan[k], m->ev_pool[k], m->ev_tail[k], m->ev_bottom[k]})
             if (e) (void)hipEventDestroy(e);
-    if (m->ev_fork2) (void)hipEventDestroy(m->ev_fork2);
+    for (hipStream_t o : m->own_stream)
+        if (o) (void)hipStreamDestroy(o);
     if (m->side) (void)hipStreamDestroy(m->side);
     delete m;
 }
@@ -646,18 +627,21 @@ rec_status rec_bind_workspace(rec_model *m, void *dev_ptr, size_t bytes, void *s
         // Default priority; the two events only order work, they carry no timing.
         if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess ||
             hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&m->ev_fork2, hipEventDisableTiming) != hipSuccess)
+            hipEventCreateWithFlags(&m->ev_join, hipEventDisableTiming) != hipSuccess)
             return REC_ERR_DEVICE;
-        for (int k = 0; k < 2; ++k)
+        for (int k = 0; k < MAX_FRAMES; ++k)
             if (hipEventCreateWithFlags(&m->ev_scan[k], hipEventDisableTiming) != hipSuccess ||
                 hipEventCreateWithFlags(&m->ev_pool[k], hipEventDisableTiming) != hipSuccess ||
-                hipEventCreateWithFlags(&m->ev_tail[k], hipEventDisableTiming) != hipSuccess)
+                hipEventCreateWithFlags(&m->ev_tail[k], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&m->ev_bottom[k], hipEventDisableTiming) != hipSuccess)
                 return REC_ERR_DEVICE;
     }
-    m->tail_pending[0] = m->tail_pending[1] = false;
+    if (m->pipeline)
+        for (hipStream_t &o : m->own_stream)
+            if (!o && hipStreamCreateWithFlags(&o, hipStreamNonBlocking) != hipSuccess) return REC_ERR_DEVICE;
+    for (bool &b : m->tail_pending) b = false;
     m->next_frame = m->last_frame = 0;
-    m->have_deferred = false;
+    m->pool_turn = 0;
     if (fc_big_prepare() != hipSuccess || chain_prepare() != hipSuccess) return REC_ERR_DEVICE;
     {   // set-up is also where the static scratch of this device is looked up
         char *unused = nullptr;
@@ -759,45 +743,43 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
     } while (0)
 
     if (m->pipeline) {
-        // Pooling (S1) on the caller's stream, everything else on the second
-        // stream: while batch i is pooled, that stream runs the interaction and
-        // Predict-FC of batch i - 1 and the scan and Bottom-FC of batch i + 1
-        // (Sec. IV-A, S-D pipeline; dependencies of Sec. III-A).  Frame k holds
-        // what this batch passes through; the batch before it used the other one.
-        // Order on the second stream: scan(i), Bottom-FC(i), then the deferred
-        // interaction and Predict-FC of batch i - 1, so that the next pooling launch
-        // never waits behind a stage that itself waits for the current one.
+        // Four queues (Sec. IV-A, S-D pipeline; dependencies of Sec. III-A): scan
+        // (S0) and Bottom-FC (S2) on the caller's stream, pooling (S1) on two
+        // streams in turn, interaction and Predict-FC (S3, S4) on a fourth.  Two
+        // pooling launches are in flight at any time, so neither the packets between
+        // launches nor the ramps of a launch leave the memory system idle; a batch
+        // owns one of four frames until its logits are written.
         const int k = m->next_frame;
         const Bufs u = bufs_at(m->ws, m->lay, k);
+        hipStream_t p = m->pool_stream[m->pool_turn] ? m->pool_stream[m->pool_turn] : m->own_stream[m->pool_turn];
         hipStream_t d = m->dense_stream ? m->dense_stream : m->side;
-        // While the caller's stream is being captured into a graph, the second
-        // stream has to fork from it before its first launch, or that launch would
-        // run at once instead of being recorded.
-        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-        REC_DEV(hipStreamIsCapturing(s, &capturing));
-        if (capturing == hipStreamCaptureStatusActive) {
-            REC_DEV(hipEventRecord(m->ev_fork2, s));
-            REC_DEV(hipStreamWaitEvent(d, m->ev_fork2, 0));
+        if (m->tail_pending[k]) {  // the batch that used this frame four calls ago
+            REC_DEV(hipStreamWaitEvent(s, m->ev_tail[k], 0));
+            m->tail_pending[k] = false;
         }
-        REC_DEV(mark(ev, EV_BEGIN, d));
-        REC_DEV(enqueue_scan(m, u, c, d));
-        REC_DEV(mark(ev, EV_SCAN_END, d));
-        REC_DEV(hipEventRecord(m->ev_scan[k], d));
+        REC_DEV(mark(ev, EV_BEGIN, s));
+        REC_DEV(enqueue_scan(m, u, c, s));
+        REC_DEV(mark(ev, EV_SCAN_END, s));
+        REC_DEV(hipEventRecord(m->ev_scan[k], s));
+        REC_DEV(hipStreamWaitEvent(p, m->ev_scan[k], 0));
+        REC_DEV(mark(ev, EV_POOL_BEGIN, p));
+        REC_DEV(enqueue_pool(m, u, c, true, p));
+        REC_DEV(mark(ev, EV_POOL_END, p));
+        REC_DEV(hipEventRecord(m->ev_pool[k], p));
         if (!m->bottom.empty()) {
-            REC_DEV(mark(ev, EV_BOTTOM_BEGIN, d));
-            REC_DEV(enqueue_bottom(m, u, c, d, ev));
+            REC_DEV(mark(ev, EV_BOTTOM_BEGIN, s));
+            REC_DEV(enqueue_bottom(m, u, c, s, ev));
         }
-        REC_DEV(hipStreamWaitEvent(s, m->ev_scan[k], 0));
-        REC_DEV(mark(ev, EV_POOL_BEGIN, s));
-        REC_DEV(enqueue_pool(m, u, c, true, s));
-        REC_DEV(mark(ev, EV_POOL_END, s));
-        REC_DEV(hipEventRecord(m->ev_pool[k], s));
-        if (enqueue_deferred(m, d) != hipSuccess) return REC_ERR_DEVICE;
-        m->have_deferred = true;
-        m->def_dense = dev_dense; m->def_logits = dev_logits; m->def_batch = batch; m->def_frame = k;
-        m->def_ev = ev;
+        REC_DEV(hipEventRecord(m->ev_bottom[k], s));
+        REC_DEV(hipStreamWaitEvent(d, m->ev_bottom[k], 0));
+        REC_DEV(hipStreamWaitEvent(d, m->ev_pool[k], 0));
+        REC_DEV(mark(ev, EV_INTERACT_BEGIN, d));
+        REC_DEV(enqueue_tail(m, u, c, d, ev));
+        REC_DEV(hipEventRecord(m->ev_tail[k], d));
+        m->tail_pending[k] = true;
         m->last_frame = k;
-        m->next_frame = k ^ 1;
+        m->next_frame = (k + 1) % MAX_FRAMES;
+        m->pool_turn ^= 1;
         if (prof) m->slot_mode[slot] = 1;
     } else {
         const Bufs u = bufs_at(m->ws, m->lay, 0);
@@ -867,10 +849,7 @@ rec_status rec_drain(rec_model *m, void *stream)
 {
     if (!m) return REC_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (m->have_deferred &&
-        enqueue_deferred(m, m->dense_stream ? m->dense_stream : m->side) != hipSuccess)
-        return REC_ERR_DEVICE;
-    for (int k = 0; k < 2; ++k)
+    for (int k = 0; k < MAX_FRAMES; ++k)
         if (m->tail_pending[k]) {
             if (hipStreamWaitEvent(s, m->ev_tail[k], 0) != hipSuccess) return REC_ERR_DEVICE;
             m->tail_pending[k] = false;
@@ -935,7 +914,7 @@ rec_status rec_set_option(rec_model *m, int32_t option, int32_t value)
         // Decides the size of the workspace: only while none is bound.
         if (m->ws) return REC_ERR_STATE;
         m->pipeline = value != 0;
-        m->lay = carve(m, m->max_batch, m->pipeline ? 2 : 1);
+        m->lay = carve(m, m->max_batch, m->pipeline ? MAX_FRAMES : 1);
         return REC_OK;
     default: return REC_ERR_ARG;
     }
@@ -944,9 +923,19 @@ rec_status rec_set_option(rec_model *m, int32_t option, int32_t value)
 rec_status rec_set_dense_stream(rec_model *m, void *stream)
 {
     if (!m) return REC_ERR_ARG;
-    for (int k = 0; k < 2; ++k)
-        if (m->tail_pending[k] || m->have_deferred) return REC_ERR_STATE;  // work is still ordered on the old one
+    for (int k = 0; k < MAX_FRAMES; ++k)
+        if (m->tail_pending[k]) return REC_ERR_STATE;  // work is still ordered on the old one
     m->dense_stream = static_cast<hipStream_t>(stream);
+    return REC_OK;
+}
+
+rec_status rec_set_pool_streams(rec_model *m, void *stream_a, void *stream_b)
+{
+    if (!m) return REC_ERR_ARG;
+    for (int k = 0; k < MAX_FRAMES; ++k)
+        if (m->tail_pending[k]) return REC_ERR_STATE;
+    m->pool_stream[0] = static_cast<hipStream_t>(stream_a);
+    m->pool_stream[1] = static_cast<hipStream_t>(stream_b);
     return REC_OK;
 }
 
@@ -955,7 +944,6 @@ rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period)
     if (!m || slots < 0 || slots > 65536 || (slots > 0 && period < 1)) return REC_ERR_ARG;
     for (hipEvent_t e : m->ev)
         if (e) (void)hipEventDestroy(e);
-    m->def_ev = nullptr;  // a deferred Predict-FC is then enqueued untimed
     m->ev.assign((size_t)slots * EV_PER_SLOT, nullptr);
     m->slot_mode.assign((size_t)slots, 0);
     m->slots = 0;
@@ -973,8 +961,6 @@ rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms)
     const long long timed = (m->forwards + m->period - 1) / m->period;  // timed forwards so far
     if (m->slots <= 0 || slot < 0 || slot >= m->slots || slot >= timed) return REC_ERR_STATE;
     hipEvent_t *ev = &m->ev[(size_t)slot * EV_PER_SLOT];
-    // A pipelined forward's last stages are enqueued by the next call or by rec_drain().
-    if (m->have_deferred && m->def_ev == ev) return REC_ERR_STATE;
     // Stage i ran between events begin[i] and end[i]; in a pipelined forward the
     // dense stages sit on another stream and have begin events of their own.
     static const int end[REC_NUM_STAGES] = {EV_SCAN_END, EV_POOL_END, EV_BOTTOM_FIRST_END, EV_BOTTOM_END,

@@ -130,3 +130,10 @@ def test_null_and_order_errors_without_device(binding):
     assert lib.rec_bind_workspace(h, 4100, 1 << 30, None) == b.REC_ERR_ARG  # misaligned
     b.rec_destroy(h)
     b.rec_destroy(None)
+    # the matrix-rate probe checks its arguments before touching the device
+    assert b.rec_probe_mfma(True, 256, 100, None) == b.REC_ERR_ARG
+    lib.rec_probe_mfma.restype = C.c_int
+    lib.rec_probe_mfma.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    assert lib.rec_probe_mfma(1, 0, 100, 4096, None) == b.REC_ERR_ARG
+    assert lib.rec_probe_mfma(1, 256, 0, 4096, None) == b.REC_ERR_ARG
+    assert lib.rec_probe_mfma(1, 1 << 20, 1, 4096, None) == b.REC_ERR_ARG

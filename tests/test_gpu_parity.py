@@ -728,3 +728,17 @@ def test_wide_bottom_layer_on_fp32_input(binding, F, B):
     assert np.abs(x0 - mirror["bottom_out"]).max() <= 2e-3 * scale
     H.check_logits(logits, exact["logits"], mirror["logits"])
     m.close()
+
+
+def test_matrix_rate_probe_runs(binding):
+    """The measurement helper behind bench.py's mfma_sustained: both operand kinds run and leave a finite checksum."""
+    say("matrix-rate probe")
+    sink = torch.full((1,), float("nan"), device="cuda")
+    for rnd in (False, True):
+        assert binding.rec_probe_mfma(rnd, 64, 50, sink) == binding.REC_OK
+        torch.cuda.synchronize()
+        assert torch.isfinite(sink).all()
+    # constant operands: every product is 1, 16 per instruction, 4 instructions per accumulator and iteration
+    assert binding.rec_probe_mfma(False, 8, 10, sink) == binding.REC_OK
+    torch.cuda.synchronize()
+    assert sink.item() == 8 * 10 * 4 * 16.0

@@ -1,7 +1,8 @@
-"""The sparse-dense pipeline (REC_OPT_PIPELINE): pooling launches back to back
-on the caller's stream, scan, Bottom-FC, interaction and Predict-FC of the
-neighbouring batches beside them on a second stream.  Same kernels as the in-order pass, so the logits must be
-bit-equal to it, and they are held to the oracle's bars as well.
+"""The sparse-dense pipeline (REC_OPT_PIPELINE): scan and Bottom-FC on the
+caller's stream, pooling launches on two streams in turn, interaction and
+Predict-FC on a fourth, four batches in flight.  Same kernels as the in-order
+pass, so the logits must be bit-equal to it, and they are held to the oracle's
+bars as well.
 """
 import numpy as np
 import pytest
@@ -30,18 +31,21 @@ def dev(batch):
             torch.from_numpy(batch.lengths).cuda())
 
 
-@pytest.mark.parametrize("name,own_dense_stream", [("tiny", True), ("tiny", False), ("mtwnd-tiny", True)])
-def test_pipelined_forwards_equal_in_order_forwards(binding, name, own_dense_stream):
-    """Nine back-to-back forwards of varying batch size, no host synchronisation
-    in between, results read after rec_drain(): bit-equal to the in-order model
-    and within the bars against the oracle."""
+@pytest.mark.parametrize("name,own_streams", [("tiny", True), ("tiny", False), ("mtwnd-tiny", True)])
+def test_pipelined_forwards_equal_in_order_forwards(binding, name, own_streams):
+    """Eleven back-to-back forwards of varying batch size (every frame of the
+    workspace is reused at least once), no host synchronisation in between,
+    results read after rec_drain(): bit-equal to the in-order model and within
+    the bars against the oracle."""
     w = synth.WORKLOADS[name]
-    say("pipeline vs in-order", name, own_dense_stream)
-    sizes = [w.batch, 37, w.batch, 1, 129, w.batch, 64, 3, w.batch]
+    say("pipeline vs in-order", name, own_streams)
+    sizes = [w.batch, 37, w.batch, 1, 129, w.batch, 64, 3, w.batch, 200, 5]
     ref, bottom, top = H.make_workload_model(binding, w)
     main = torch.cuda.Stream()
-    side = torch.cuda.Stream() if own_dense_stream else None
-    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side)
+    side = torch.cuda.Stream() if own_streams else None
+    pools = (torch.cuda.Stream(), torch.cuda.Stream()) if own_streams else (None, None)
+    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side,
+                                     pool_streams=pools)
     # Left to itself a pipelined model runs every layer as a kernel of its own (the
     # chain kernel's 8-wave blocks find no room beside pooling), which sums in a
     # different order than a chain: compare like with like.
@@ -65,7 +69,7 @@ def test_pipelined_forwards_equal_in_order_forwards(binding, name, own_dense_str
     assert pm.check() == (binding.REC_OK, -1) and ref.check() == (binding.REC_OK, -1)
     for i, (g, wnt) in enumerate(zip(got, want)):
         assert np.array_equal(g.numpy(), wnt), i
-    for i in (0, 1, 3, 8):
+    for i in (0, 1, 3, 8, 10):
         b = batches[i]
         fwd = orc.forward_towers if w.interaction == "concat" else orc.forward
         exact = fwd(b.dense, tabs, b.indices, b.lengths, bottom, top)
@@ -81,7 +85,9 @@ def test_pipelined_forwards_equal_in_order_forwards(binding, name, own_dense_str
 def test_pipelined_results_are_ordered_behind_drain(binding):
     """Work enqueued on the caller's stream behind rec_drain() sees the logits of
     every call so far, also when drains and forwards alternate, with the
-    library's own second stream and with one the caller brings."""
+    library's own streams and with ones the caller brings; and every input is
+    read in stream order: the uploads sit on the caller's stream behind a long
+    kernel, the forwards are enqueued while nothing has arrived yet."""
     w = synth.WORKLOADS["tiny"]
     say("pipeline: ordering behind drain")
     ref, _, _ = H.make_workload_model(binding, w)
@@ -90,13 +96,23 @@ def test_pipelined_results_are_ordered_behind_drain(binding):
     data = [dev(b) for b in batches]
     want = [ref.forward(*d).cpu().numpy() for d in data]
     torch.cuda.synchronize()
-    for mode, side in ((1, torch.cuda.Stream()), (2, None)):
-        pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side)
+    pinned = [[torch.from_numpy(a).pin_memory() for a in (b.dense, b.indices, b.lengths)] for b in batches]
+    for mode, side, pools in ((1, torch.cuda.Stream(), (torch.cuda.Stream(), torch.cuda.Stream())),
+                              (2, None, (None, None))):
+        pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side,
+                                         pool_streams=pools)
         main = torch.cuda.Stream()
         outs = [torch.empty(w.batch, dtype=torch.float32, device="cuda") for _ in data]
         snaps = {}
+        # device buffers that hold garbage until the copies on `main` have run
+        late = [[torch.full(t.shape, -7, dtype=t.dtype, device="cuda") for t in p] for p in pinned]
+        torch.cuda.synchronize()
         with torch.cuda.stream(main):
-            for i, (d, o) in enumerate(zip(data, outs)):
+            torch.cuda._sleep(20_000_000)               # a few milliseconds in front of the uploads
+            for p, dv in zip(pinned, late):
+                for src, dst in zip(p, dv):
+                    dst.copy_(src, non_blocking=True)
+            for i, (d, o) in enumerate(zip(late, outs)):
                 pm.forward(*d, o)
                 if i in (0, 3):                        # a drain in the middle of the run
                     pm.drain()
@@ -117,7 +133,7 @@ def test_pipelined_results_are_ordered_behind_drain(binding):
 
 
 def test_pipelined_stage_timing(binding):
-    """Stage events of a pipelined forward: readable after rec_drain(), every stage positive."""
+    """Stage events of a pipelined forward: every stage positive."""
     w = synth.WORKLOADS["tiny"]
     say("pipeline: stage events")
     pm, _, _ = H.make_workload_model(binding, w, pipeline=True)
@@ -125,7 +141,6 @@ def test_pipelined_stage_timing(binding):
     pm.set_profiling(3, 1)
     for _ in range(3):
         pm.forward(*d)
-    assert binding.rec_stage_ms(pm.handle, 2)[0] == binding.REC_ERR_STATE     # its last stages are not enqueued yet
     pm.drain()
     torch.cuda.synchronize()
     for slot in range(3):
@@ -136,8 +151,8 @@ def test_pipelined_stage_timing(binding):
 
 
 def test_pipelined_forwards_in_a_graph(binding):
-    """Three pipelined forwards and the drain recorded into one HIP graph (the second
-    stream forks from and joins the captured one through the library's events);
+    """Three pipelined forwards and the drain recorded into one HIP graph (the other
+    streams fork from and join the captured one through the library's events);
     every replay, with eager work in between, gives the in-order bits."""
     w = synth.WORKLOADS["tiny"]
     say("pipeline: graph replay")
@@ -177,14 +192,18 @@ def test_pipelined_edge_calls(binding):
     pm.forward(d, i, l, out)
     # a batch of zero samples enqueues nothing and leaves the outstanding call alone
     assert binding.rec_forward(pm.handle, d, i, l, 0, 0, out) == binding.REC_OK
-    # the second stream cannot be swapped while work is outstanding on it
+    # streams cannot be swapped while work is outstanding on them
     assert binding.rec_set_dense_stream(pm.handle, None) == binding.REC_ERR_STATE
+    assert binding.rec_set_pool_streams(pm.handle, None, None) == binding.REC_ERR_STATE
     pm.drain()
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), want)
     side = torch.cuda.Stream()
     assert binding.rec_set_dense_stream(pm.handle, side) == binding.REC_OK
     pm.dense_stream = side
+    pool_a = torch.cuda.Stream()
+    assert binding.rec_set_pool_streams(pm.handle, pool_a, None) == binding.REC_OK
+    pm.pool_streams = (pool_a, None)
     # hot-row lists: the LDS-cached pooling kernel inside the pipeline, same sums
     hot = synth.profile_hot_rows(w, [3, 4], 64)
     for t in range(w.num_tables):
@@ -218,15 +237,16 @@ def test_pipelined_faults_are_reported(binding):
 
 
 def test_full_size_pipelined_whole_batches_against_oracle(binding):
-    """rmc2 at full size through the pipeline on two streams, four batches back
+    """rmc2 at full size through the pipeline on four streams, twelve batches back
     to back (the benchmark's launch configuration): every sample of the first
-    and the last batch against the oracle, all four bit-equal to in-order forwards."""
+    and the last batch against the oracle, all bit-equal to in-order forwards."""
     w = synth.WORKLOADS["rmc2"]
     say("full-size pipelined", w.name)
     ref, bottom, top = H.make_workload_model(binding, w)
     ref.set_option(binding.REC_OPT_FUSE_MLP, 0)
-    main, side = torch.cuda.Stream(), torch.cuda.Stream()
-    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side)
+    main, side, pool_a, pool_b = (torch.cuda.Stream() for _ in range(4))
+    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=side,
+                                     pool_streams=(pool_a, pool_b))
     batches = [synth.draw_batch(w, 20 + i) for i in range(4)]
     data = [dev(b) for b in batches]
     want = [ref.forward(*d).cpu().numpy() for d in data]
