@@ -86,12 +86,12 @@ __device__ inline void load_a_chunk(AChunk<false> &c, const void *A, long long r
 // the epilogue contracts act(C) with a weight vector - the one-output last
 // layer - and writes one fp32 logit per row.
 //
-// The small tiles with two k-tiles in flight are the forms that run beside a
-// pooling launch (FcProblem::corun): they are held to 128 registers, the part of
-// a SIMD's register file that eight pooling waves leave free, so that a wave of
-// theirs needs nothing but a wave slot.
+// The small tiles with two k-tiles in flight, and the 128 x 128 tile with one,
+// are the forms that run beside a pooling launch (FcProblem::corun): they are
+// held to 128 registers, the part of a SIMD's register file that eight pooling
+// waves leave free, so that a wave of theirs needs nothing but a wave slot.
 template <int BM, int BN, int WAVES_M, int P, bool A_F32, bool OUT_F32, bool FUSE_DOT>
-__global__ __launch_bounds__(FC_THREADS, (P == 2 && BM * BN <= 4096) ? 4 : 1) void fc_kernel(const void *__restrict__ A0, int lda,
+__global__ __launch_bounds__(FC_THREADS, ((P == 2 && BM * BN <= 4096) || P == 1) ? 4 : 1) void fc_kernel(const void *__restrict__ A0, int lda,
                                                         long long a_stride, int M, int K, int Kpad,
                                                         const FcGroups groups, int relu,
                                                         void *__restrict__ C0, int ldc,
@@ -374,6 +374,12 @@ hipError_t launch_fc(const FcProblem &a, hipStream_t s)
     if (a.num_cus > 0 && fc_big_applies(a, a.num_cus)) return launch_fc_big(a, a.num_cus, s);
     // Large tiles only where they still give every compute unit a block.
     const long long big_blocks = (long long)a.groups * (Npad / 128) * ((M + 127) / 128);
+    // Beside pooling what a launch costs is the wave slots it holds and the lines
+    // it pulls through the L1s, not its own duration: few large tiles, even if
+    // they leave compute units without a block (rmc2's first Predict-FC layer:
+    // 128 blocks instead of 512, 3 us less per pipelined step).
+    // (bf16 input only: with fp32 staging registers the tile does not fit 128 registers.)
+    if (a.corun && !a.a_f32 && Npad % 128 == 0 && big_blocks >= 64) return launch_tile<128, 128, 2, 1>(a, s);
     if (Npad % 128 == 0 && big_blocks >= 256) return launch_tile<128, 128, 2, 2>(a, s);
     const long long mid_blocks = (long long)a.groups * (Npad / 64) * ((M + 63) / 64);
     if (Npad % 128 == 0 && mid_blocks < 256)
