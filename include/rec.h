@@ -226,7 +226,7 @@ REC_API rec_status rec_forward_static(rec_model *m, const float *dev_dense, cons
                               const int32_t *dev_lengths, int32_t batch, int64_t nnz,
                               float *dev_logits, int64_t *dev_fault, void *stream);
 
-/* Waits for `stream` (and, pipelined, for the outstanding dense stages), reads
+/* Waits for `stream` (and, pipelined, for every outstanding stage), reads
  * and clears the device error record.  Returns REC_OK,
  * REC_ERR_LENGTHS (first_bad_pos = position in lengths of the first negative
  * one, or -1 when only the total disagreed with nnz) or REC_ERR_INDEX_RANGE
