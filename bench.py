@@ -115,6 +115,29 @@ def compulsory_pool_bytes(w, batch) -> int:
     return uniq * w.emb_dim * elt + batch.nnz * 4 + (bags + 1) * 4 + bags * w.emb_dim * out_elt
 
 
+def repeats_within_chunks(w, batch) -> dict:
+    """How many lookups repeat an id that the same wave already holds: the pooling
+    kernel takes a bag 64 ids at a time, 8 rows per wave-wide load.  What loading
+    each distinct id of a chunk once (and scaling by its count) could save, before
+    the cost of finding the repeats."""
+    import numpy as np
+    lengths = batch.lengths.astype(np.int64)
+    bag_of = np.repeat(np.arange(lengths.size, dtype=np.int64), lengths)
+    starts = np.concatenate(([0], np.cumsum(lengths)[:-1]))
+    pos = np.arange(batch.nnz, dtype=np.int64) - starts[bag_of]
+    chunk = bag_of * 4 + pos // 64                      # bags hold at most 200 ids: 4 chunks
+    key = np.sort(chunk << 32 | batch.indices[:batch.nnz].astype(np.int64))
+    first = np.ones(key.size, dtype=bool)
+    first[1:] = key[1:] != key[:-1]
+    n_chunks = int(chunk.max()) + 1
+    total = np.bincount(chunk, minlength=n_chunks)
+    distinct = np.bincount(key[first] >> 32, minlength=n_chunks)
+    loads, loads_distinct = ((total + 7) // 8).sum(), ((distinct + 7) // 8).sum()
+    return {"lookups_repeating_an_id_of_their_chunk": float(1.0 - distinct.sum() / total.sum()),
+            "wave_wide_row_loads_saved": float(1.0 - loads_distinct / loads),
+            "what": "batch 0; chunk = the 64 ids of a bag a wave holds at a time, 8 rows per wave-wide load"}
+
+
 def cpu_baseline(w, batches, bottom, top, n_samples: int) -> dict:
     """The CPU oracle, as it stands, on the first n_samples samples of each of
     the given batches (a bounded sample: tens of core-seconds of CPU work)."""
@@ -741,6 +764,8 @@ def main() -> int:
                                "HBM peak; the binding comparison is the uniform-id twin under `roofline`")
         for k in ("frac", "achieved", "bound"):
             pool_detail.pop(k)
+        if w.pooling[0] != "fixed" or w.pooling[1] > 1:
+            pool_detail["id_repeats"] = repeats_within_chunks(w, host_batches[0])
         extra["roofline_zipf"] = pool_detail
     roofline = None if skewed and w.interaction == "dot" else this_leg
 
