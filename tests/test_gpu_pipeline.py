@@ -269,3 +269,37 @@ def test_full_size_pipelined_whole_batches_against_oracle(binding):
     pm.close()
     ref.close()
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name", ["rmc1", "rmc3", "mtwnd"])
+def test_full_size_pipelined_other_workloads_equal_in_order(binding, name):
+    """The other workloads at full size through the pipeline, as the benchmark's
+    short legs run them (row loads streaming where the ids are uniform, wide
+    layers beside pooling): six batches back to back, bit-equal to in-order
+    forwards, which the parity tests hold to the oracle."""
+    w = synth.WORKLOADS[name]
+    say("full-size pipelined", w.name)
+    ref, _, _ = H.make_workload_model(binding, w)
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    pm, _, _ = H.make_workload_model(binding, w, share_tables=ref, pipeline=True, dense_stream=streams[3],
+                                     pool_streams=(streams[1], streams[2]))
+    for mm in (ref, pm):
+        mm.set_option(binding.REC_OPT_FUSE_MLP, 0)
+        mm.set_option(binding.REC_OPT_STREAM_ROWS, int(w.index_dist[0] == "uniform"))
+    batches = [synth.draw_batch(w, 40 + i) for i in range(3)]
+    data = [dev(b) for b in batches]
+    shape = (w.batch,) if w.towers == 1 else (w.batch, w.towers)
+    want = [ref.forward(*d).cpu().numpy() for d in data]
+    outs = [torch.full(shape, float("nan"), dtype=torch.float32, device="cuda") for _ in range(6)]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(streams[0]):
+        for i, o in enumerate(outs):
+            pm.forward(*data[i % 3], o)
+        pm.drain()
+    streams[0].synchronize()
+    assert pm.check() == (binding.REC_OK, -1) and ref.check() == (binding.REC_OK, -1)
+    for i, o in enumerate(outs):
+        assert np.array_equal(o.cpu().numpy(), want[i % 3]), i
+    pm.close()
+    ref.close()
+    torch.cuda.empty_cache()
