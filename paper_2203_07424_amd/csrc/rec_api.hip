@@ -292,9 +292,21 @@ hipError_t enqueue_bottom(const rec_model *m, const Bufs &u, const Call &c, hipS
 // S0 and S1.  With hot lists registered (and use_hot), hot rows are served from
 // LDS.  In the concatenation model the sums go straight into the Predict-FC
 // input rows.
+// A concatenation model without Bottom-FC has the dense part of its Predict-FC
+// input rows written by spare blocks of the scan: one launch less in front of S4.
+bool concat_rides_on_scan(const rec_model *m)
+{
+    return m->interaction == REC_INTERACT_CONCAT && m->bottom.empty();
+}
+
 hipError_t enqueue_scan(const rec_model *m, const Bufs &u, const Call &c, hipStream_t s)
 {
-    return launch_scan(c.lengths, m->T * c.B, c.nnz, u.offsets, u.tile_sums, u.err, s);
+    ConcatDense job;
+    if (concat_rides_on_scan(m)) {
+        job.x0 = c.dense; job.ldx0 = m->F; job.w0 = m->w0; job.B = c.B;
+        job.z_bf16 = u.act[0]; job.width = m->z_width; job.ldz = m->z_ld;
+    }
+    return launch_scan(c.lengths, m->T * c.B, c.nnz, u.offsets, u.tile_sums, u.err, job, s);
 }
 
 hipError_t enqueue_pool(const rec_model *m, const Bufs &u, const Call &c, bool use_hot, hipStream_t s)
@@ -340,9 +352,10 @@ hipError_t enqueue_tail(const rec_model *m, const Bufs &u, const Call &c, hipStr
     const float *x0 = m->bottom.empty() ? c.dense : u.x0;
     const int x0_ld = m->bottom.empty() ? m->F : m->x0_ld;
     // S3 -> act[0], row stride z_ld, zero filled up to it
-    if (concat)
-        REC_TRY(launch_concat_dense(x0, x0_ld, m->w0, B, u.act[0], m->z_width, m->z_ld, s));
-    else
+    if (concat) {
+        if (!concat_rides_on_scan(m))
+            REC_TRY(launch_concat_dense(x0, x0_ld, m->w0, B, u.act[0], m->z_width, m->z_ld, s));
+    } else
         REC_TRY(launch_interact(x0, x0_ld, u.pooled, B, T, D, u.act[0], m->z_ld, s));
     REC_TRY(mark(ev, EV_INTERACT_END, s));
     // S4: the towers run side by side, their hidden activations in adjacent

@@ -40,8 +40,17 @@ hipError_t launch_clear_err(ErrRecord *err, hipStream_t s);
 
 // S0. offsets[k] = min(sum_{j<k} max(len[j], 0), nnz), k = 0..n; block_sums is
 // scratch of ceil(n / SCAN_TILE) int64 entries.
+// With a ConcatDense job (x0 != null) extra blocks of the second launch also do
+// the work of launch_concat_dense(), which a model without Bottom-FC can start
+// this early: its x0 is the dense input.
+struct ConcatDense {
+    const float *x0 = nullptr;
+    int ldx0 = 0, w0 = 0, B = 0;
+    void *z_bf16 = nullptr;
+    int width = 0, ldz = 0;
+};
 hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *offsets,
-                       long long *block_sums, ErrRecord *err, hipStream_t s);
+                       long long *block_sums, ErrRecord *err, const ConcatDense &job, hipStream_t s);
 
 // Where S1 leaves the sum of bag (t, b): fp32 pooled[b][t][:], or (z != null,
 // concatenation model) narrowed to bf16 at z[b][col0 + t * D ...], row stride ldz.

@@ -8,6 +8,7 @@
 // lengths themselves (5x slower, a single block pulls only tens of GB/s); tile
 // totals reduced by each pooling wave (+28 us of pooling for -3 us of scan);
 // a last-block-done ticket (its device-scope fences cost more than a launch).
+#include <algorithm>
 #include "rec_internal.h"
 
 namespace rec {
@@ -66,8 +67,26 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_tile_offsets(const int32_t 
                                                                   int n, long long nnz,
                                                                   const long long *__restrict__ tile_sums,
                                                                   int32_t *__restrict__ offsets,
-                                                                  ErrRecord *err)
+                                                                  ErrRecord *err, int tiles,
+                                                                  const ConcatDense job)
 {
+    if ((int)blockIdx.x >= tiles) {
+        // Blocks past the scan's tiles: dense part of the Predict-FC input rows of a
+        // concatenation model, narrowed, and the zero padding behind each row.
+        __bf16 *z = static_cast<__bf16 *>(job.z_bf16);
+        const int per_row = job.w0 + (job.ldz - job.width);
+        const long long total = (long long)job.B * per_row;
+        const long long stride = (long long)(gridDim.x - tiles) * SCAN_THREADS;
+        for (long long i = (long long)(blockIdx.x - tiles) * SCAN_THREADS + threadIdx.x; i < total; i += stride) {
+            const long long b = i / per_row;
+            const int c = (int)(i - b * per_row);
+            if (c < job.w0)
+                z[b * job.ldz + c] = (__bf16)job.x0[b * job.ldx0 + c];
+            else
+                z[b * job.ldz + job.width + (c - job.w0)] = (__bf16)0.0f;
+        }
+        return;
+    }
     // One extra word per 32 keeps the 8-per-thread strided reads off one bank.
     __shared__ int s_tile[SCAN_TILE + SCAN_TILE / 32];
     __shared__ long long s_w[SCAN_THREADS / 64];
@@ -156,10 +175,15 @@ hipError_t launch_clear_err(ErrRecord *err, hipStream_t s)
 }
 
 hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *offsets,
-                       long long *block_sums, ErrRecord *err, hipStream_t s)
+                       long long *block_sums, ErrRecord *err, const ConcatDense &job, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
     const int tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
+    int extra = 0;
+    if (job.x0) {
+        const long long total = (long long)job.B * (job.w0 + job.ldz - job.width);
+        extra = (int)std::min<long long>((total + 8 * SCAN_THREADS - 1) / (8 * SCAN_THREADS), 256);
+    }
     const long long *sums = block_sums;  // never read by the single tile of a small input
     if (tiles > 1) {
         hipLaunchKernelGGL(scan_tile_sums, dim3(tiles), dim3(SCAN_THREADS), 0, s, lengths, n,
@@ -167,8 +191,8 @@ hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *of
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(scan_tile_offsets, dim3(tiles), dim3(SCAN_THREADS), 0, s, lengths, n, nnz,
-                       sums, offsets, err);
+    hipLaunchKernelGGL(scan_tile_offsets, dim3(tiles + extra), dim3(SCAN_THREADS), 0, s, lengths, n, nnz,
+                       sums, offsets, err, tiles, job);
     return hipGetLastError();
 }
 
