@@ -862,11 +862,12 @@ rec_status rec_drain(rec_model *m, void *stream)
 {
     if (!m) return REC_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    for (int k = 0; k < MAX_FRAMES; ++k)
-        if (m->tail_pending[k]) {
-            if (hipStreamWaitEvent(s, m->ev_tail[k], 0) != hipSuccess) return REC_ERR_DEVICE;
-            m->tail_pending[k] = false;
-        }
+    // Every batch's last stage runs on the one dense stream, in order: the event
+    // of the latest call stands for all of them.
+    if (m->tail_pending[m->last_frame] &&
+        hipStreamWaitEvent(s, m->ev_tail[m->last_frame], 0) != hipSuccess)
+        return REC_ERR_DEVICE;
+    for (bool &p : m->tail_pending) p = false;
     return REC_OK;
 }
 
