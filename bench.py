@@ -470,38 +470,81 @@ def short_leg(torch, binding, synth, np, name, args, dev, streams):
     return res
 
 
-def sweep_leg(torch, binding, synth, np, w0, sizes, iters, sla_ms, dev, stream, warmup=10):
-    """Batch-size sweep: per-batch latency, one batch in flight (closed loop: queuing
-    delay excluded), and the latency-bounded throughput (Sec. II-B) under sla_ms."""
+PIPELINE_WINDOW = 4   # batches in flight in the pipelined closed loop: one per workspace frame
+
+
+def windowed_pipeline_profile(torch, np, pm, streams, db, outs, n, warmup):
+    """Closed loop through the pipelined model with PIPELINE_WINDOW batches in
+    flight: batch i is enqueued once batch i - PIPELINE_WINDOW has finished.  A
+    batch's latency runs from the moment the caller's stream reaches its call to
+    the end of its last stage (an event on the dense stream)."""
+    total = n + warmup
+    begin = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
+    end = [torch.cuda.Event(enable_timing=True) for _ in range(total)]
+    t = 0.0
+    torch.cuda.synchronize()
+    with torch.cuda.stream(streams[0]):
+        for i in range(total):
+            if i >= PIPELINE_WINDOW:
+                end[i - PIPELINE_WINDOW].synchronize()
+            if i == warmup:
+                t = time.perf_counter()
+            begin[i].record(streams[0])
+            pm.forward(*db[i % len(db)], outs[i % len(outs)])
+            end[i].record(pm.dense_stream)
+        pm.drain()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t
+    lat = np.array([begin[i].elapsed_time(end[i]) for i in range(warmup, total)])
+    return {"p50": float(np.percentile(lat, 50)), "p99": float(np.percentile(lat, 99)), "max": float(lat.max()),
+            "mean": float(lat.mean()), "seconds": dt, "iterations": n}
+
+
+def sweep_leg(torch, binding, synth, np, w0, sizes, iters, sla_ms, dev, streams, warmup=10):
+    """Batch-size sweep: per-batch latency with one batch in flight and, through
+    the pipelined model, with PIPELINE_WINDOW in flight (closed loops: queuing delay
+    excluded), and the latency-bounded throughput (Sec. II-B) under sla_ms."""
     t0 = time.time()
     m, _, _ = build_model(binding, synth, torch, w0, max(sizes))
+    pm, _, _ = build_model(binding, synth, torch, w0, max(sizes), share_tables=m, pipeline=True,
+                           dense_stream=streams[3], pool_streams=(streams[1], streams[2]))
     log(f"  {w0.name} resident ({time.time() - t0:.1f} s)")
     rows = []
     for B in sizes:
         w = w0.with_batch(B)
         hb, db = make_batches(torch, synth, w, 2, 1000, dev)
-        out = new_logits(torch, w, B, dev)
-        lat = latency_profile(torch, np, m, stream, db, out, iters, warmup)
-        assert m.check() == (binding.REC_OK, -1)
+        outs = [new_logits(torch, w, B, dev) for _ in range(PIPELINE_WINDOW)]
+        lat = latency_profile(torch, np, m, streams[0], db, outs[0], iters, warmup)
+        pl = windowed_pipeline_profile(torch, np, pm, streams, db, outs, iters, warmup)
+        assert m.check() == (binding.REC_OK, -1) and pm.check() == (binding.REC_OK, -1)
         rows.append({"batch": B, "mean_nnz": float(np.mean([b.nnz for b in hb])), "p50_ms": lat["p50"],
-                     "p99_ms": lat["p99"], "max_ms": lat["max"], "samples_per_s": B / (lat["mean"] * 1e-3)})
+                     "p99_ms": lat["p99"], "max_ms": lat["max"], "samples_per_s": B / (lat["mean"] * 1e-3),
+                     "pipelined": {"in_flight": PIPELINE_WINDOW, "p50_ms": pl["p50"], "p99_ms": pl["p99"],
+                                   "max_ms": pl["max"], "samples_per_s": B * iters / pl["seconds"]}})
         log(f"  B={B}: p50 {lat['p50']:.3f} ms p99 {lat['p99']:.3f} ms "
-            f"{rows[-1]['samples_per_s'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
-        del db, out
+            f"{rows[-1]['samples_per_s'] / 1e6:.2f} M samples/s; pipelined p99 {pl['p99']:.3f} ms "
+            f"{rows[-1]['pipelined']['samples_per_s'] / 1e6:.2f} M samples/s ({time.time() - t0:.1f} s)")
+        del db, outs
+    pm.close()
     m.close()
 
     def bounded(limit):
-        ok = [r for r in rows if r["p99_ms"] <= limit]
-        return max(ok, key=lambda r: r["samples_per_s"]) if ok else None
+        cand = [(r["samples_per_s"], r["batch"], "one batch in flight") for r in rows if r["p99_ms"] <= limit]
+        cand += [(r["pipelined"]["samples_per_s"], r["batch"], f"pipelined, {PIPELINE_WINDOW} batches in flight")
+                 for r in rows if r["pipelined"]["p99_ms"] <= limit]
+        return max(cand) if cand else None
     best, best50 = bounded(sla_ms), bounded(50.0)
     return {"workload": workload_string(w0), "dtype": dtype_string(w0), "sla_ms": sla_ms,
-            "latency_bounded_samples_per_s": best["samples_per_s"] if best else None,
-            "best_batch": best["batch"] if best else None,
-            "at_the_paper_s_50_ms_bound": {"samples_per_s": best50["samples_per_s"] if best50 else None,
-                                           "best_batch": best50["batch"] if best50 else None},
+            "latency_bounded_samples_per_s": best[0] if best else None,
+            "best_batch": best[1] if best else None, "best_mode": best[2] if best else None,
+            "at_the_paper_s_50_ms_bound": {"samples_per_s": best50[0] if best50 else None,
+                                           "best_batch": best50[1] if best50 else None,
+                                           "best_mode": best50[2] if best50 else None},
             "iterations_per_batch_size": iters,
-            "note": "closed loop, one batch in flight; per-batch latency includes the host's launch calls; "
-                    "queuing delay excluded; p99 over the timed iterations",
+            "note": "closed loops: one batch in flight (latency includes the host's launch calls), and the "
+                    f"pipelined model with {PIPELINE_WINDOW} batches in flight (latency from the caller's stream "
+                    "reaching the call to the end of the batch's last stage); queuing delay excluded; p99 over "
+                    "the timed iterations",
             "sweep": rows}
 
 
@@ -516,15 +559,17 @@ def latency_sweep(args) -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     r = sweep_leg(torch, binding, synth, np, w0, sizes, args.sweep_iters, args.sla_ms, dev,
-                  torch.cuda.Stream(), args.warmup)
+                  pick_concurrent_streams(torch, dev, 4), args.warmup)
     best = next((x for x in r["sweep"] if x["batch"] == r["best_batch"]), None)
+    if best and r["best_mode"] != "one batch in flight":
+        best = best["pipelined"]
     out = {"metric": f"latency-bounded samples/s per GPU at p99 <= {args.sla_ms} ms per batch",
            "value": r["latency_bounded_samples_per_s"], "unit": "samples/s", "n_gpus": 1,
            "steps": args.sweep_iters, "warmup": args.warmup,
            "ms_per_step": best["p50_ms"] if best else None, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": dtype_string(w0), "data": "synthetic",
-           "config": {"workload": r["workload"], "best_batch": r["best_batch"], "sla_ms": args.sla_ms,
-                      "note": r["note"]},
+           "config": {"workload": r["workload"], "best_batch": r["best_batch"], "mode": r["best_mode"],
+                      "sla_ms": args.sla_ms, "note": r["note"]},
            "at_the_paper_s_50_ms_bound": r["at_the_paper_s_50_ms_bound"], "sweep": r["sweep"]}
     print(json.dumps(out), flush=True)
     return 0
@@ -860,7 +905,7 @@ def main() -> int:
         if free >= need:
             others["rmc2-large"] = sweep_leg(torch, binding, synth, np, wl,
                                              [int(x) for x in args.sweep_batches.split(",")],
-                                             args.sweep_iters, args.sla_ms, dev, streams[0])
+                                             args.sweep_iters, args.sla_ms, dev, streams)
         else:
             others["rmc2-large"] = {"skipped": f"needs {need >> 30} GiB of device memory, {free >> 30} GiB free"}
         extra["other_workloads"] = others

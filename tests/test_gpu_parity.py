@@ -643,6 +643,28 @@ def test_large_capacity_variant_sampled_against_oracle(binding):
         logits = H.run(m, batch)
         if B == 4096:
             whole_batch_check(binding, m, w, batch, logits, bottom, top, w.name)
+            # the sweep's pipelined leg: the same batch six times through the pipelined
+            # model on four streams, bit-equal to in-order forwards with the same launches
+            say("large-capacity workload, pipelined")
+            streams = [torch.cuda.Stream() for _ in range(4)]
+            pm, _, _ = H.make_workload_model(binding, w0, max_batch=4096, share_tables=m, pipeline=True,
+                                             dense_stream=streams[3], pool_streams=(streams[1], streams[2]))
+            for mm in (m, pm):
+                mm.set_option(binding.REC_OPT_FUSE_MLP, 0)
+            want = H.run(m, batch)
+            d = [torch.from_numpy(a).cuda() for a in (batch.dense, batch.indices, batch.lengths)]
+            outs = [torch.full((B,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(6)]
+            torch.cuda.synchronize()
+            with torch.cuda.stream(streams[0]):
+                for o in outs:
+                    pm.forward(*d, o)
+                pm.drain()
+            streams[0].synchronize()
+            assert pm.check() == (binding.REC_OK, -1)
+            for i, o in enumerate(outs):
+                assert np.array_equal(o.cpu().numpy(), want), i
+            pm.close()
+            m.set_option(binding.REC_OPT_FUSE_MLP, 1)
             continue
         assert m.check() == (binding.REC_OK, -1)
         pick = np.array([0, 1, 255, 256, B - 2, B - 1])
