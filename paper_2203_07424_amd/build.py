@@ -36,7 +36,8 @@ SAN_FLAGS = ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsaniti
 def _compile(src: str, force: bool, sanitize: bool = False) -> str:
     s = os.path.join(CSRC, src)
     o = os.path.join(OBJ_SAN if sanitize else OBJ, src + ".o")
-    deps = [s, os.path.join(CSRC, "rec_internal.h"), os.path.join(ROOT, "include", "rec.h"),
+    deps = [s, os.path.join(CSRC, "rec_internal.h"), os.path.join(CSRC, "mlp_chain_body.h"),
+            os.path.join(ROOT, "include", "rec.h"),
             os.path.join(ROOT, "include", "rec_synth.h"), os.path.join(ROOT, "include", "rec_probe.h"),
             os.path.abspath(__file__)]
     if not force and os.path.exists(o) and all(os.path.getmtime(o) >= os.path.getmtime(d) for d in deps):

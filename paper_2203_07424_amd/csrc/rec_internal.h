@@ -49,8 +49,16 @@ struct ConcatDense {
     void *z_bf16 = nullptr;
     int width = 0, ldz = 0;
 };
+// With `rider` (a stack of fully connected layers that fits the on-chip kernel,
+// fp32 input, one stack) further blocks of the second launch run that stack:
+// Bottom-FC does not depend on the sparse side (Sec. III-A), so it can share a
+// launch with the scan instead of costing one of its own.
+struct ChainProblem;
 hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *offsets,
-                       long long *block_sums, ErrRecord *err, const ConcatDense &job, hipStream_t s);
+                       long long *block_sums, ErrRecord *err, const ConcatDense &job,
+                       const ChainProblem *rider, hipStream_t s);
+// Once per process and device, before the first launch (not under stream capture).
+hipError_t scan_prepare();
 
 // Where S1 leaves the sum of bag (t, b): fp32 pooled[b][t][:], or (z != null,
 // concatenation model) narrowed to bf16 at z[b][col0 + t * D ...], row stride ldz.
@@ -138,9 +146,11 @@ struct ChainProblem {
     const float *dot_w[MAX_GROUPS];
     const float *dot_bias[MAX_GROUPS];
     float *dot_out; int dot_ld;
-    int ld_lds, a_vec;  // filled in by launch_mlp_chain()
+    int ld_lds, a_vec;  // filled in by chain_finalize()
 };
 bool chain_layer_fits(int Kpad, int Npad);
+// Checks p and completes it (LDS row pitch, whether wide input loads apply) into a.
+hipError_t chain_finalize(const ChainProblem &p, ChainProblem &a);
 hipError_t launch_mlp_chain(const ChainProblem &p, hipStream_t s);
 // Once per process and device, before the first launch (not under stream capture).
 hipError_t chain_prepare();

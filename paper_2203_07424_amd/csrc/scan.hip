@@ -9,7 +9,7 @@
 // totals reduced by each pooling wave (+28 us of pooling for -3 us of scan);
 // a last-block-done ticket (its device-scope fences cost more than a launch).
 #include <algorithm>
-#include "rec_internal.h"
+#include "mlp_chain_body.h"
 
 namespace rec {
 
@@ -63,40 +63,40 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_tile_sums(const int32_t *__
     if (threadIdx.x == 0) tile_sums[blockIdx.x] = sum;
 }
 
-__global__ __launch_bounds__(SCAN_THREADS) void scan_tile_offsets(const int32_t *__restrict__ len,
-                                                                  int n, long long nnz,
-                                                                  const long long *__restrict__ tile_sums,
-                                                                  int32_t *__restrict__ offsets,
-                                                                  ErrRecord *err, int tiles,
-                                                                  const ConcatDense job)
+// Dense part of the Predict-FC input rows of a concatenation model, narrowed,
+// and the zero padding behind each row: block `b` of `nb` blocks.
+__device__ inline void concat_dense_block(const ConcatDense &job, int b, int nb)
 {
-    if ((int)blockIdx.x >= tiles) {
-        // Blocks past the scan's tiles: dense part of the Predict-FC input rows of a
-        // concatenation model, narrowed, and the zero padding behind each row.
-        __bf16 *z = static_cast<__bf16 *>(job.z_bf16);
-        const int per_row = job.w0 + (job.ldz - job.width);
-        const long long total = (long long)job.B * per_row;
-        const long long stride = (long long)(gridDim.x - tiles) * SCAN_THREADS;
-        for (long long i = (long long)(blockIdx.x - tiles) * SCAN_THREADS + threadIdx.x; i < total; i += stride) {
-            const long long b = i / per_row;
-            const int c = (int)(i - b * per_row);
-            if (c < job.w0)
-                z[b * job.ldz + c] = (__bf16)job.x0[b * job.ldx0 + c];
-            else
-                z[b * job.ldz + job.width + (c - job.w0)] = (__bf16)0.0f;
-        }
-        return;
+    __bf16 *z = static_cast<__bf16 *>(job.z_bf16);
+    const int per_row = job.w0 + (job.ldz - job.width);
+    const long long total = (long long)job.B * per_row;
+    const long long stride = (long long)nb * blockDim.x;
+    for (long long i = (long long)b * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const long long r = i / per_row;
+        const int c = (int)(i - r * per_row);
+        if (c < job.w0)
+            z[r * job.ldz + c] = (__bf16)job.x0[r * job.ldx0 + c];
+        else
+            z[r * job.ldz + job.width + (c - job.w0)] = (__bf16)0.0f;
     }
+}
+
+// Offsets of tile `tile`; the threads with threadIdx.x < SCAN_THREADS call it,
+// all of them.
+__device__ inline void scan_offsets_tile(const int32_t *__restrict__ len, int n, long long nnz,
+                                         const long long *__restrict__ tile_sums,
+                                         int32_t *__restrict__ offsets, ErrRecord *err, int tile)
+{
     // One extra word per 32 keeps the 8-per-thread strided reads off one bank.
     __shared__ int s_tile[SCAN_TILE + SCAN_TILE / 32];
     __shared__ long long s_w[SCAN_THREADS / 64];
     __shared__ long long s_wave_excl[SCAN_THREADS / 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const long long base = (long long)blockIdx.x * SCAN_TILE;
+    const long long base = (long long)tile * SCAN_TILE;
 
     // Sum of all earlier tiles.
     long long before = 0;
-    for (int j = tid; j < (int)blockIdx.x; j += SCAN_THREADS) before += tile_sums[j];
+    for (int j = tid; j < tile; j += SCAN_THREADS) before += tile_sums[j];
     before = block_sum(before, s_w);
 
     // Coalesced load of this tile; negative lengths count as 0.
@@ -166,6 +166,42 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_tile_offsets(const int32_t 
     }
 }
 
+// Second launch of the scan: blocks [0, tiles) write the offsets, the blocks
+// behind them do a concatenation model's dense copy.
+__global__ __launch_bounds__(SCAN_THREADS) void scan_tile_offsets(const int32_t *__restrict__ len,
+                                                                  int n, long long nnz,
+                                                                  const long long *__restrict__ tile_sums,
+                                                                  int32_t *__restrict__ offsets,
+                                                                  ErrRecord *err, int tiles,
+                                                                  const ConcatDense job)
+{
+    if ((int)blockIdx.x < tiles)
+        scan_offsets_tile(len, n, nnz, tile_sums, offsets, err, blockIdx.x);
+    else
+        concat_dense_block(job, blockIdx.x - tiles, gridDim.x - tiles);
+}
+
+// The same with a stack of fully connected layers riding along: blocks of
+// chain::CH_THREADS threads; behind the scan's and the copy's blocks come
+// chain_grid_x blocks that each take chain::CH_ROWS samples through the stack.
+// A scan block uses its first SCAN_THREADS threads; the waves of the others end
+// at once (a barrier counts only the waves of a group that have not ended).
+__global__ __launch_bounds__(chain::CH_THREADS) void scan_offsets_ride_kernel(
+    const int32_t *__restrict__ len, int n, long long nnz, const long long *__restrict__ tile_sums,
+    int32_t *__restrict__ offsets, ErrRecord *err, int tiles, const ConcatDense job, int extra,
+    const ChainProblem a, int chain_grid_x)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int b = blockIdx.x;
+    if (b < tiles) {
+        if (threadIdx.x < SCAN_THREADS) scan_offsets_tile(len, n, nnz, tile_sums, offsets, err, b);
+    } else if (b < tiles + extra) {
+        concat_dense_block(job, b - tiles, extra);
+    } else {
+        chain::mlp_chain_block<true>(a, smem, b - tiles - extra, 0, chain_grid_x);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_clear_err(ErrRecord *err, hipStream_t s)
@@ -174,8 +210,16 @@ hipError_t launch_clear_err(ErrRecord *err, hipStream_t s)
     return hipGetLastError();
 }
 
+hipError_t scan_prepare()
+{
+    const int most = (int)chain::chain_lds_bytes(CHAIN_MAX_WIDTH + chain::CH_LDS_PAD);
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(scan_offsets_ride_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, most);
+}
+
 hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *offsets,
-                       long long *block_sums, ErrRecord *err, const ConcatDense &job, hipStream_t s)
+                       long long *block_sums, ErrRecord *err, const ConcatDense &job,
+                       const ChainProblem *rider, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
     const int tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
@@ -190,6 +234,17 @@ hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *of
                            block_sums);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+    }
+    if (rider && rider->M > 0) {
+        if (!rider->a_f32 || rider->groups != 1) return hipErrorInvalidValue;
+        ChainProblem a;
+        const hipError_t e = chain_finalize(*rider, a);
+        if (e != hipSuccess) return e;
+        const int chain_grid_x = (a.M + chain::CH_ROWS - 1) / chain::CH_ROWS;
+        hipLaunchKernelGGL(scan_offsets_ride_kernel, dim3(tiles + extra + chain_grid_x),
+                           dim3(chain::CH_THREADS), chain::chain_lds_bytes(a.ld_lds), s, lengths, n, nnz, sums,
+                           offsets, err, tiles, job, extra, a, chain_grid_x);
+        return hipGetLastError();
     }
     hipLaunchKernelGGL(scan_tile_offsets, dim3(tiles + extra), dim3(SCAN_THREADS), 0, s, lengths, n, nnz,
                        sums, offsets, err, tiles, job);

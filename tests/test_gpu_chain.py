@@ -201,3 +201,28 @@ def test_full_size_workload_with_every_possible_chain(binding, name):
     assert np.isfinite(forced).all()
     m.close()
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("name,B", [("tiny", 256), ("tiny", 1), ("tiny", 77), ("rmc1", 1024), ("rmc2", 4096)])
+def test_bottom_fc_riding_on_the_scan_equals_its_own_launch(binding, name, B):
+    """An in-order forward runs a chainable Bottom-FC inside the scan's second
+    launch.  With REC_OPT_OVERLAP_DENSE the same stack is a launch of its own (on
+    the side stream): same kernel body, same sums, so the bits must agree - for
+    the Bottom-FC output and for the logits - and the offsets must still be right."""
+    w = synth.WORKLOADS[name].with_batch(B)
+    say("Bottom-FC on the scan", name, B)
+    ride, _, _ = H.make_workload_model(binding, w)
+    own, _, _ = H.make_workload_model(binding, w, share_tables=ride)
+    own.set_option(binding.REC_OPT_OVERLAP_DENSE, 1)
+    for seed in (3, 4):
+        b = synth.draw_batch(w, seed)
+        d = [torch.from_numpy(a).cuda() for a in (b.dense, b.indices, b.lengths)]
+        got, want = ride.forward(*d), own.forward(*d)
+        torch.cuda.synchronize()
+        assert ride.check() == (binding.REC_OK, -1) and own.check() == (binding.REC_OK, -1)
+        assert torch.equal(ride.debug_bottom_out(), own.debug_bottom_out())
+        assert torch.equal(got, want)
+        assert np.array_equal(np.diff(ride.debug_offsets().cpu().numpy().astype(np.int64)), b.lengths)
+    ride.close()
+    own.close()
+    torch.cuda.empty_cache()
