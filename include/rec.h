@@ -321,7 +321,9 @@ REC_API rec_status rec_drain(rec_model *m, void *stream);
  * ms[REC_NUM_STAGES]; REC_ERR_STATE if that slot has not been recorded.
  * With REC_OPT_OVERLAP_DENSE the first Bottom-FC stage is only the time the
  * caller's stream waited for Bottom-FC after pooling had finished, and the
- * second reads about zero.  With REC_OPT_PIPELINE every stage is bracketed on
+ * second reads about zero.  An in-order forward whose Bottom-FC runs inside the
+ * scan's second launch (a stack that fits the on-chip kernel) reports it under
+ * REC_STAGE_SCAN and gives 0 for both Bottom-FC stages.  With REC_OPT_PIPELINE every stage is bracketed on
  * the stream it runs on (a stage's time then includes whatever shared the
  * device with it). */
 REC_API rec_status rec_set_profiling(rec_model *m, int32_t slots, int32_t period);

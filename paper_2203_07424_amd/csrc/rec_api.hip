@@ -94,7 +94,7 @@ struct rec_model {
 
     // Stage timing: forward number i records into slot i % slots.
     std::vector<hipEvent_t> ev;  // slots * EV_PER_SLOT
-    std::vector<char> slot_mode; // per slot: 1 if it was recorded by a pipelined forward
+    std::vector<char> slot_mode; // per slot: 1 recorded by a pipelined forward, 2 in order with Bottom-FC inside the scan's launch
     int slots = 0, period = 1;
     long long forwards = 0;      // forwards seen since profiling was switched on
 
@@ -841,7 +841,7 @@ rec_status rec_forward(rec_model *m, const float *dev_dense, const int32_t *dev_
         } else {
             REC_DEV(enqueue_in_order(m, u, c, true, s, ev));
         }
-        if (prof) m->slot_mode[slot] = 0;
+        if (prof) m->slot_mode[slot] = !m->overlap_dense && bottom_rides_on_scan(m) ? 2 : 0;
     }
 #undef REC_DEV
     if (m->slots > 0) ++m->forwards;
@@ -1011,12 +1011,13 @@ rec_status rec_stage_ms(rec_model *m, int32_t slot, float *ms)
     static const int begin_pipelined[REC_NUM_STAGES] = {EV_BEGIN, EV_POOL_BEGIN, EV_BOTTOM_BEGIN,
                                                         EV_BOTTOM_FIRST_END, EV_INTERACT_BEGIN,
                                                         EV_INTERACT_END, EV_TOP_FIRST_END};
-    const int *begin = m->slot_mode[slot] ? begin_pipelined : begin_in_order;
+    const int *begin = m->slot_mode[slot] == 1 ? begin_pipelined : begin_in_order;
     if (hipEventSynchronize(ev[EV_END]) != hipSuccess) return REC_ERR_DEVICE;
     for (int i = 0; i < REC_NUM_STAGES; ++i) {
         ms[i] = 0.0f;
-        if (m->slot_mode[slot] && (i == REC_STAGE_BOTTOM_FIRST || i == REC_STAGE_BOTTOM_REST) && m->bottom.empty())
-            continue;
+        const bool bottom_stage = i == REC_STAGE_BOTTOM_FIRST || i == REC_STAGE_BOTTOM_REST;
+        if (bottom_stage && ((m->slot_mode[slot] == 1 && m->bottom.empty()) || m->slot_mode[slot] == 2))
+            continue;  // no launch of its own: nothing to time
         if (hipEventElapsedTime(&ms[i], ev[begin[i]], ev[end[i]]) != hipSuccess) return REC_ERR_DEVICE;
     }
     return REC_OK;

@@ -226,3 +226,29 @@ def test_bottom_fc_riding_on_the_scan_equals_its_own_launch(binding, name, B):
     ride.close()
     own.close()
     torch.cuda.empty_cache()
+
+
+def test_stage_timing_says_where_bottom_fc_ran(binding):
+    """In order, a chainable Bottom-FC has no launch of its own: both of its stages
+    read 0 and the scan's stage holds it.  Layer by layer (REC_OPT_FUSE_MLP = 0)
+    every stage has an interval of its own."""
+    w = synth.WORKLOADS["tiny"]
+    say("stage timing, Bottom-FC on the scan")
+    m, _, _ = H.make_workload_model(binding, w)
+    b = synth.draw_batch(w, 9)
+    d = [torch.from_numpy(a).cuda() for a in (b.dense, b.indices, b.lengths)]
+    for fuse, riding in ((1, True), (0, False)):
+        m.set_option(binding.REC_OPT_FUSE_MLP, fuse)
+        m.set_profiling(2, 1)
+        for _ in range(2):
+            m.forward(*d)
+        torch.cuda.synchronize()
+        for slot in range(2):
+            ms = m.stage_ms(slot)
+            for k, v in ms.items():
+                if riding and k in ("bottom_first", "bottom_rest"):
+                    assert v == 0.0, ms
+                else:
+                    assert v > 0.0, ms
+        m.set_profiling(0)
+    m.close()
