@@ -94,9 +94,21 @@ __device__ inline void scan_offsets_tile(const int32_t *__restrict__ len, int n,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const long long base = (long long)tile * SCAN_TILE;
 
-    // Sum of all earlier tiles.
+    // Sum of all earlier tiles: from their sums, or (no sums: a short input whose
+    // first launch was left out) from the lengths themselves.
     long long before = 0;
-    for (int j = tid; j < tile; j += SCAN_THREADS) before += tile_sums[j];
+    if (tile_sums) {
+        for (int j = tid; j < tile; j += SCAN_THREADS) before += tile_sums[j];
+    } else {
+        // base is a multiple of SCAN_TILE: SCAN_ITEMS loads per thread and tile, all in flight together
+        for (long long k0 = 0; k0 < base; k0 += SCAN_TILE) {
+            int v[SCAN_ITEMS];
+#pragma unroll
+            for (int i = 0; i < SCAN_ITEMS; ++i) v[i] = len[k0 + i * SCAN_THREADS + tid];
+#pragma unroll
+            for (int i = 0; i < SCAN_ITEMS; ++i) before += v[i] > 0 ? v[i] : 0;
+        }
+    }
     before = block_sum(before, s_w);
 
     // Coalesced load of this tile; negative lengths count as 0.
@@ -228,14 +240,19 @@ hipError_t launch_scan(const int32_t *lengths, int n, long long nnz, int32_t *of
         const long long total = (long long)job.B * (job.w0 + job.ldz - job.width);
         extra = (int)std::min<long long>((total + 8 * SCAN_THREADS - 1) / (8 * SCAN_THREADS), 256);
     }
-    const long long *sums = block_sums;  // never read by the single tile of a small input
-    if (tiles > 1) {
+    // With a stack riding along the second launch lasts as long as the stack, so
+    // for a few tiles its scan blocks have the time to add up the earlier lengths
+    // themselves and the first launch can go (alone, that was measured no faster
+    // than two launches at 5 tiles and slower beyond).
+    const bool has_rider = rider && rider->M > 0;
+    const long long *sums = has_rider && tiles <= 8 ? nullptr : block_sums;
+    if (tiles > 1 && sums) {
         hipLaunchKernelGGL(scan_tile_sums, dim3(tiles), dim3(SCAN_THREADS), 0, s, lengths, n,
                            block_sums);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    if (rider && rider->M > 0) {
+    if (has_rider) {
         if (!rider->a_f32 || rider->groups != 1) return hipErrorInvalidValue;
         ChainProblem a;
         const hipError_t e = chain_finalize(*rider, a);

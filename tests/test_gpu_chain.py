@@ -252,3 +252,37 @@ def test_stage_timing_says_where_bottom_fc_ran(binding):
                     assert v > 0.0, ms
         m.set_profiling(0)
     m.close()
+
+
+@pytest.mark.parametrize("B", [300, 1000, 1024, 1100])
+def test_short_scan_in_one_launch_with_faults(binding, B):
+    """Up to 8 scan tiles with a Bottom-FC riding along: the scan is one launch
+    whose blocks add up the earlier lengths themselves.  Offsets bit-exact, a
+    negative length in a later tile and a wrong total reported as ever."""
+    w = synth.WORKLOADS["tiny"].with_batch(B)          # 8 tables: 2, 4, 4 and 5 tiles
+    say("one-launch scan", B)
+    m, _, _ = H.make_workload_model(binding, w)
+    b = synth.draw_batch(w, 21)
+    off, rc, _ = orc.offsets(b.lengths)
+    assert rc == 0
+    H.run(m, b)
+    assert m.check() == (binding.REC_OK, -1)
+    assert np.array_equal(m.debug_offsets().cpu().numpy().astype(np.int64), off)
+    # a negative length in the last tile: counted as zero, its position reported
+    neg = b.lengths.copy()
+    at = neg.size - 7
+    cut = int(neg[at])
+    neg[at] = -cut - 1
+    start = int(b.lengths[:at].sum())
+    idx = np.concatenate([b.indices[:start], b.indices[start + cut:]])
+    H.run(m, synth.Batch(b.dense, idx, neg))
+    off2, rc2, bad = orc.offsets(neg)
+    assert rc2 == -1 and bad == at
+    assert m.check() == (binding.REC_ERR_LENGTHS, at)
+    assert np.array_equal(m.debug_offsets().cpu().numpy().astype(np.int64), off2)
+    # total != nnz: reported, offsets clamped
+    logits = H.run(m, synth.Batch(b.dense, b.indices[:-5], b.lengths))
+    assert m.check() == (binding.REC_ERR_LENGTHS, -1)
+    assert np.isfinite(logits).all()
+    assert m.debug_offsets().cpu().numpy().max() == b.indices.size - 5
+    m.close()
